@@ -1,0 +1,161 @@
+"""ctypes front end of the PrefixKV CPU oracle (``prefixkv_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  The product package never imports this module, and this
+module never imports the product package.
+
+All functions take and return NumPy arrays on the host.  Floating inputs are fp32 arrays whose
+values are already representable in the workload's storage dtype.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "prefixkv_oracle.c"
+_LIB = _HERE / "libprefixkv_oracle.so"
+
+NONFINITE, NEGATIVE, ZERO_LAYER, RANGE = 1, 2, 4, 8
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (fp64 arithmetic must stay in source order: no -ffast-math)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(".so.tmp%d" % os.getpid())
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp",
+                               "-ffp-contract=off", "-o", str(tmp), str(_SRC), "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(str(build()))
+        _lib.pkvo_threads.restype = C.c_int
+        _lib.pkvo_decode_attn.restype = C.c_int
+        _lib.pkvo_sort_prefix_layer.restype = C.c_int
+    return _lib
+
+
+def threads() -> int:
+    return int(lib().pkvo_threads())
+
+
+def _p(a, ty=C.c_void_p):
+    return None if a is None else a.ctypes.data_as(ty)
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def importance(q, k, scale, want_lse: bool = False):
+    """q [B,L,H,N,D], k [B,L,Hkv,N,D], scale [L] -> importance [B,L,N] f32 (and lse [B,L,H,N] f64)."""
+    q, k, scale = _f32(q), _f32(k), _f32(scale)
+    B, L, H, N, D = q.shape
+    Hkv = k.shape[2]
+    assert k.shape == (B, L, Hkv, N, D) and H % Hkv == 0 and scale.shape == (L,)
+    imp = np.empty((B, L, N), dtype=np.float32)
+    lse = np.empty((B, L, H, N), dtype=np.float64) if want_lse else None
+    lib().pkvo_importance(B, L, H, Hkv, N, D, _p(q), _p(k), _p(scale), _p(imp), _p(lse))
+    return (imp, lse) if want_lse else imp
+
+
+def sort_prefix_layer(imp):
+    """One layer: importance [N] -> (status, order [N] i32, cum [N] u64, prefix [N] f32)."""
+    imp = _f32(imp)
+    N = imp.shape[0]
+    order = np.zeros(N, dtype=np.int32)
+    cum = np.zeros(N, dtype=np.uint64)
+    prefix = np.zeros(N, dtype=np.float32)
+    st = lib().pkvo_sort_prefix_layer(N, _p(imp), _p(order), _p(cum), _p(prefix))
+    return int(st), order, cum, prefix
+
+
+def search(cum, budget_tokens: int, tol_tokens: int = 0, max_iters: int = 64, fixup: bool = True):
+    """One sequence: cum [L,N] u64 -> (lengths [L] i32, p, iters, raw_total)."""
+    cum = np.ascontiguousarray(cum, dtype=np.uint64)
+    L, N = cum.shape
+    assert max_iters >= 1
+    lengths = np.zeros(L, dtype=np.int32)
+    p = C.c_double(0.0)
+    it = C.c_int32(0)
+    raw = C.c_int64(0)
+    lib().pkvo_search(L, N, _p(cum), C.c_int64(budget_tokens), C.c_int64(tol_tokens), max_iters,
+                      int(bool(fixup)), _p(lengths), C.byref(p), C.byref(it), C.byref(raw))
+    return lengths, p.value, it.value, raw.value
+
+
+def select(imp, budget_tokens: int, tol_tokens: int = 0, max_iters: int = 64, fixup: bool = True):
+    """importance [B,L,N] -> dict(order, cum, prefix, lengths, p, iters, raw_total, status)."""
+    imp = _f32(imp)
+    B, L, N = imp.shape
+    assert max_iters >= 1
+    out = dict(order=np.zeros((B, L, N), np.int32), cum=np.zeros((B, L, N), np.uint64),
+               prefix=np.zeros((B, L, N), np.float32), lengths=np.zeros((B, L), np.int32),
+               p=np.zeros(B, np.float64), iters=np.zeros(B, np.int32),
+               raw_total=np.zeros(B, np.int64), status=np.zeros(B, np.int32))
+    lib().pkvo_select(B, L, N, _p(imp), C.c_int64(budget_tokens), C.c_int64(tol_tokens), max_iters,
+                      int(bool(fixup)), _p(out["order"]), _p(out["cum"]), _p(out["prefix"]),
+                      _p(out["lengths"]), _p(out["p"]), _p(out["iters"]), _p(out["raw_total"]),
+                      _p(out["status"]))
+    return out
+
+
+def compact(k, v, order, lengths, decode_capacity: int):
+    """k,v [B,L,Hkv,N,D]; order [B,L,N]; lengths [B,L] -> ragged cache dict.
+    kc/vc are flat f32 arrays of sum(caps)*Hkv*D elements (segment (b,l) = [Hkv][cap][D] at token
+    offset seg_off[b,l]); slots that hold nothing are NaN."""
+    k, v = _f32(k), _f32(v)
+    B, L, Hkv, N, D = k.shape
+    order = np.ascontiguousarray(order, dtype=np.int32)
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    total = int(lengths.sum()) + B * L * decode_capacity
+    out = dict(seg_off=np.zeros((B, L), np.int64), caps=np.zeros((B, L), np.int32),
+               kc=np.full(total * Hkv * D, np.nan, np.float32),
+               vc=np.full(total * Hkv * D, np.nan, np.float32),
+               kept_pos=np.full(total, -1, np.int32), lens=np.zeros((B, L), np.int32),
+               Hkv=Hkv, D=D)
+    lib().pkvo_compact(B, L, Hkv, N, D, _p(k), _p(v), _p(order), _p(lengths), decode_capacity,
+                       _p(out["seg_off"]), _p(out["caps"]), _p(out["kc"]), _p(out["vc"]),
+                       _p(out["kept_pos"]), _p(out["lens"]))
+    return out
+
+
+def decode_attn(cache, q, k_new, v_new, scale, l0=None, l1=None, out_bf16: bool = False):
+    """One decode step over layers [l0,l1) on a cache dict from compact(); mutates the cache
+    (append) and returns out [B,L,H,D] f32 (layers outside the range are NaN)."""
+    q, scale = _f32(q), _f32(scale)
+    B, L, H, D = q.shape
+    Hkv = cache["Hkv"]
+    l0 = 0 if l0 is None else l0
+    l1 = L if l1 is None else l1
+    if k_new is not None:
+        k_new, v_new = _f32(k_new), _f32(v_new)
+        assert k_new.shape == (B, L, Hkv, D) and v_new.shape == (B, L, Hkv, D)
+    out = np.full((B, L, H, D), np.nan, np.float32)
+    rc = lib().pkvo_decode_attn(B, L, H, Hkv, D, l0, l1, _p(q), _p(k_new), _p(v_new), _p(scale),
+                                _p(cache["kc"]), _p(cache["vc"]), _p(cache["seg_off"]),
+                                _p(cache["caps"]), _p(cache["lens"]), _p(out), int(out_bf16))
+    if rc != 0:
+        raise ValueError("append exceeds segment capacity")
+    return out
+
+
+def segment(cache, name: str, b: int, l: int):
+    """View of segment (b,l) of 'kc'/'vc' as [Hkv, cap, D], or of 'kept_pos' as [cap]."""
+    off = int(cache["seg_off"][b, l])
+    cap = int(cache["caps"][b, l])
+    if name == "kept_pos":
+        return cache["kept_pos"][off:off + cap]
+    Hkv, D = cache["Hkv"], cache["D"]
+    return cache[name][off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)

@@ -1,0 +1,375 @@
+/*
+ * PrefixKV CPU oracle -- TEST INFRASTRUCTURE, not a product path.
+ *
+ * A plain, slow, fp64 implementation of the five stages of the PrefixKV hot path, written from the
+ * paper's definitions (Sec. 3.2 "Layer-wise KV Cache Importance Distribution", Sec. 3.3 "PrefixKV",
+ * Eq. 1, Algorithm 1).  It shares no code with the HIP library and is only used by the tests, by
+ * the smoke check and by the benchmark's cpu_baseline leg.
+ *
+ * Conventions: all pointers are host memory, arrays are dense row-major.  Inputs arrive as fp32
+ * values that are already exactly representable in the storage dtype (the workload generator does
+ * the rounding); all arithmetic below is fp64 unless a step says otherwise.
+ *
+ * OpenMP is used only across independent units (b,l,h), (b,l) or b; every reduction that crosses
+ * units is done serially in a fixed order, so results do not depend on the thread count.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { PKVO_NONFINITE = 1, PKVO_NEGATIVE = 2, PKVO_ZERO_LAYER = 4, PKVO_RANGE = 8 };
+
+int pkvo_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 1 -- importance (Sec. 3.2).
+ * a[m][n] = exp(scale*q_m.k_n) / sum_{j<=m} exp(scale*q_m.k_j)   for n <= m   (causal score matrix)
+ * I[n]    = mean over the H query heads of sum_{m>=n} a[m][n]               (importance metric)
+ * Query head h reads KV head h / (H/Hkv).  The paper's literal formula has scale = 1.
+ * q [B,L,H,N,D], k [B,L,Hkv,N,D], scale [L] -> importance [B,L,N] (fp32 cast at the very end).
+ * If lse_out != NULL it receives log(sum_j exp(scale*q_m.k_j)) per row, [B,L,H,N] fp64.
+ * ------------------------------------------------------------------------------------------- */
+void pkvo_importance(int B, int L, int H, int Hkv, int N, int D, const float *q, const float *k,
+                     const float *scale, float *importance, double *lse_out) {
+    const int grp = H / Hkv;
+    const long units = (long)B * L * H;
+    double *colsum = (double *)calloc((size_t)units * N, sizeof(double));
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)N);
+#pragma omp for schedule(dynamic, 1)
+        for (long u = 0; u < units; ++u) {
+            const int h = (int)(u % H);
+            const int l = (int)((u / H) % L);
+            const int b = (int)(u / ((long)H * L));
+            const float *qh = q + (((size_t)b * L + l) * H + h) * (size_t)N * D;
+            const float *kh = k + (((size_t)b * L + l) * Hkv + h / grp) * (size_t)N * D;
+            double *cs = colsum + (size_t)u * N;
+            const double sc = (double)scale[l];
+            for (int m = 0; m < N; ++m) {
+                double mx = -INFINITY;
+                for (int n = 0; n <= m; ++n) {
+                    double dot = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        dot += (double)qh[(size_t)m * D + d] * (double)kh[(size_t)n * D + d];
+                    s[n] = sc * dot;
+                    if (s[n] > mx) mx = s[n];
+                }
+                double den = 0.0;
+                for (int n = 0; n <= m; ++n) {
+                    s[n] = exp(s[n] - mx);
+                    den += s[n];
+                }
+                for (int n = 0; n <= m; ++n) cs[n] += s[n] / den;
+                if (lse_out) lse_out[(size_t)u * N + m] = mx + log(den);
+            }
+        }
+        free(s);
+    }
+    /* Average over heads, fixed order h = 0..H-1. */
+    for (long bl = 0; bl < (long)B * L; ++bl)
+        for (int n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int h = 0; h < H; ++h) acc += colsum[((size_t)bl * H + h) * N + n];
+            importance[(size_t)bl * N + n] = (float)(acc / (double)H);
+        }
+    free(colsum);
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 2 -- priority sequence and cumulative priority (Sec. 3.2).
+ * The priority sequence is the positions sorted by importance, descending; equal values keep the
+ * lower position first (-0.0 counts as +0.0).  The normalised cumulative priority P^o is kept as an
+ * exact integer pair (C_k, T): weight w = floor(importance * 2^36) as u64, C_k = sum of the first k
+ * sorted weights, T = C_N, so P^{k/N} = C_k / T with no rounding anywhere.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    float v;
+    int32_t pos;
+} pkvo_item;
+
+static int pkvo_item_cmp(const void *a, const void *b) {
+    const pkvo_item *x = (const pkvo_item *)a, *y = (const pkvo_item *)b;
+    if (x->v > y->v) return -1;
+    if (x->v < y->v) return 1;
+    return (x->pos > y->pos) - (x->pos < y->pos);
+}
+
+/* One layer.  Returns status bits; on a non-zero status the outputs are unspecified. */
+int pkvo_sort_prefix_layer(int N, const float *imp, int32_t *order, uint64_t *cum, float *prefix) {
+    int status = 0;
+    for (int n = 0; n < N; ++n) {
+        if (isnan(imp[n]) || isinf(imp[n])) status |= PKVO_NONFINITE;
+        else if (imp[n] < 0.0f) status |= PKVO_NEGATIVE;
+    }
+    if (status) return status;
+    pkvo_item *it = (pkvo_item *)malloc(sizeof(pkvo_item) * (size_t)N);
+    for (int n = 0; n < N; ++n) {
+        it[n].v = imp[n] == 0.0f ? 0.0f : imp[n]; /* folds -0.0 into +0.0 */
+        it[n].pos = n;
+    }
+    qsort(it, (size_t)N, sizeof(pkvo_item), pkvo_item_cmp);
+    const double two36 = 68719476736.0;
+    const uint64_t lim = (uint64_t)1 << 53;
+    uint64_t c = 0;
+    for (int j = 0; j < N; ++j) {
+        order[j] = it[j].pos;
+        double wd = floor((double)it[j].v * two36);
+        if (wd >= 9007199254740992.0) { status |= PKVO_RANGE; wd = 0.0; }
+        c += (uint64_t)wd;
+        if (c > lim) status |= PKVO_RANGE;
+        cum[j] = c;
+    }
+    free(it);
+    if (status) return status;
+    if (c == 0) return PKVO_ZERO_LAYER;
+    if (prefix)
+        for (int j = 0; j < N; ++j) prefix[j] = (float)((double)cum[j] / (double)c);
+    return 0;
+}
+
+/* Prefix length of one layer for threshold p (Sec. 3.3: R_l = min{o | P_l^o >= p}), in tokens:
+ * the smallest k in 1..N with C_k >= p*T; p >= 1 keeps everything by definition. */
+static int pkvo_layer_len(int N, const uint64_t *cum, double p) {
+    if (p >= 1.0) return N;
+    const double thr = p * (double)cum[N - 1];
+    int k = 1;
+    for (int j = 1; j <= N - 1; ++j)
+        if ((double)cum[j - 1] < thr) ++k;
+    return k;
+}
+
+typedef struct {
+    uint64_t rem;
+    int l;
+} pkvo_rem;
+
+static int pkvo_rem_desc(const void *a, const void *b) {
+    const pkvo_rem *x = (const pkvo_rem *)a, *y = (const pkvo_rem *)b;
+    if (x->rem != y->rem) return x->rem > y->rem ? -1 : 1;
+    return (x->l > y->l) - (x->l < y->l);
+}
+static int pkvo_rem_asc(const void *a, const void *b) {
+    const pkvo_rem *x = (const pkvo_rem *)a, *y = (const pkvo_rem *)b;
+    if (x->rem != y->rem) return x->rem < y->rem ? -1 : 1;
+    return (x->l > y->l) - (x->l < y->l);
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 3 -- Algorithm 1 (binary search for the retention ratio p) for ONE sequence, followed by
+ * the "scale the configuration to meet the budget" step of Sec. 3.3's last paragraph.
+ * cum [L,N]; budget/tol in tokens.  Outputs lengths[L], *p, *iters, *raw_total (sum of lengths of
+ * the last evaluated p, before scaling).
+ * ------------------------------------------------------------------------------------------- */
+void pkvo_search(int L, int N, const uint64_t *cum, int64_t budget, int64_t tol, int max_iters,
+                 int fixup, int32_t *lengths, double *p_out, int32_t *iters_out,
+                 int64_t *raw_total_out) {
+    if (budget <= L) { /* nothing below one vector per layer: o starts at 1/N */
+        for (int l = 0; l < L; ++l) lengths[l] = 1;
+        *p_out = 0.0; *iters_out = 0; *raw_total_out = L;
+        return;
+    }
+    if (budget >= (int64_t)L * N) { /* budget of 100%: no compression */
+        for (int l = 0; l < L; ++l) lengths[l] = N;
+        *p_out = 1.0; *iters_out = 0; *raw_total_out = (int64_t)L * N;
+        return;
+    }
+    double p1 = 0.0, p2 = 1.0, p = 0.5;
+    int64_t K = 0;
+    int iters = 0;
+    for (int it = 1; it <= max_iters; ++it) {
+        const double mid = 0.5 * (p1 + p2);
+        if (mid == p1 || mid == p2) break; /* interval cannot shrink any more */
+        p = mid;
+        K = 0;
+        for (int l = 0; l < L; ++l) {
+            lengths[l] = pkvo_layer_len(N, cum + (size_t)l * N, p);
+            K += lengths[l];
+        }
+        iters = it;
+        const int64_t delta = K - budget;
+        if (llabs(delta) <= tol) break;
+        if (delta < 0) p1 = p; else p2 = p;
+    }
+    *p_out = p; *iters_out = iters; *raw_total_out = K;
+    if (!fixup || K == budget) return;
+
+    /* Proportional rescale of the configuration to the budget, largest remainder first. */
+    pkvo_rem *r = (pkvo_rem *)malloc(sizeof(pkvo_rem) * (size_t)L);
+    int64_t sum = 0;
+    for (int l = 0; l < L; ++l) {
+        const uint64_t num = (uint64_t)lengths[l] * (uint64_t)budget;
+        int64_t base = (int64_t)(num / (uint64_t)K);
+        if (base < 1) base = 1;
+        if (base > N) base = N;
+        r[l].rem = num % (uint64_t)K;
+        r[l].l = l;
+        lengths[l] = (int32_t)base;
+        sum += base;
+    }
+    int64_t dlt = budget - sum;
+    if (dlt > 0) {
+        qsort(r, (size_t)L, sizeof(pkvo_rem), pkvo_rem_desc);
+        for (int i = 0; dlt > 0; i = (i + 1) % L)
+            if (lengths[r[i].l] < N) { lengths[r[i].l] += 1; --dlt; }
+    } else if (dlt < 0) {
+        qsort(r, (size_t)L, sizeof(pkvo_rem), pkvo_rem_asc);
+        for (int i = 0; dlt < 0; i = (i + 1) % L)
+            if (lengths[r[i].l] > 1) { lengths[r[i].l] -= 1; ++dlt; }
+    }
+    free(r);
+}
+
+/* Stages 2+3 for a batch: importance [B,L,N] -> order, cum, prefix (may be NULL), lengths [B,L],
+ * p [B], iters [B], raw_total [B], status [B].  A sequence with a non-zero status gets
+ * lengths = 0, p = 0, iters = 0, raw_total = 0. */
+void pkvo_select(int B, int L, int N, const float *importance, int64_t budget, int64_t tol,
+                 int max_iters, int fixup, int32_t *order, uint64_t *cum, float *prefix,
+                 int32_t *lengths, double *p, int32_t *iters, int64_t *raw_total, int32_t *status) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int st = 0;
+        for (int l = 0; l < L; ++l) {
+            const size_t o = ((size_t)b * L + l) * N;
+            st |= pkvo_sort_prefix_layer(N, importance + o, order + o, cum + o,
+                                         prefix ? prefix + o : NULL);
+        }
+        status[b] = st;
+        if (st) {
+            for (int l = 0; l < L; ++l) lengths[(size_t)b * L + l] = 0;
+            p[b] = 0.0; iters[b] = 0; raw_total[b] = 0;
+        } else {
+            pkvo_search(L, N, cum + (size_t)b * L * N, budget, tol, max_iters, fixup,
+                        lengths + (size_t)b * L, p + b, iters + b, raw_total + b);
+        }
+    }
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 4a -- compaction (Sec. 3.2: the top R_l proportion is retained in each head of layer l).
+ * The kept set of (b,l) is the first lengths[b,l] entries of its priority sequence; it is stored in
+ * ascending original position.  Ragged layout: segment (b,l) starts at token offset seg_off[b,l]
+ * (exclusive scan of caps = lengths + decode_capacity in (b,l) order) and holds [Hkv][cap][D].
+ * kc/vc must hold sum(caps)*Hkv*D floats; slots beyond the kept ones are left untouched.
+ * ------------------------------------------------------------------------------------------- */
+static int pkvo_i32_cmp(const void *a, const void *b) {
+    const int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+void pkvo_compact(int B, int L, int Hkv, int N, int D, const float *k, const float *v,
+                  const int32_t *order, const int32_t *lengths, int decode_capacity,
+                  int64_t *seg_off, int32_t *caps, float *kc, float *vc, int32_t *kept_pos,
+                  int32_t *lens) {
+    int64_t off = 0;
+    for (long bl = 0; bl < (long)B * L; ++bl) {
+        caps[bl] = lengths[bl] + decode_capacity;
+        seg_off[bl] = off;
+        off += caps[bl];
+        lens[bl] = lengths[bl];
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bl = 0; bl < (long)B * L; ++bl) {
+        const int kl = lengths[bl];
+        const int cap = caps[bl];
+        int32_t *kp = kept_pos + seg_off[bl];
+        memcpy(kp, order + (size_t)bl * N, sizeof(int32_t) * (size_t)kl);
+        qsort(kp, (size_t)kl, sizeof(int32_t), pkvo_i32_cmp);
+        for (int h = 0; h < Hkv; ++h) {
+            const float *ksrc = k + ((size_t)bl * Hkv + h) * (size_t)N * D;
+            const float *vsrc = v + ((size_t)bl * Hkv + h) * (size_t)N * D;
+            float *kdst = kc + ((size_t)seg_off[bl] * Hkv + (size_t)h * cap) * D;
+            float *vdst = vc + ((size_t)seg_off[bl] * Hkv + (size_t)h * cap) * D;
+            for (int j = 0; j < kl; ++j) {
+                memcpy(kdst + (size_t)j * D, ksrc + (size_t)kp[j] * D, sizeof(float) * (size_t)D);
+                memcpy(vdst + (size_t)j * D, vsrc + (size_t)kp[j] * D, sizeof(float) * (size_t)D);
+            }
+        }
+    }
+}
+
+/* Round-to-nearest-even to bfloat16, returned as the fp32 value it represents. */
+static float pkvo_round_bf16(double x) {
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return f; /* NaN */
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Stage 4b -- one decode step for layers [l0,l1) (Sec. 3.1: the newest token's query interacts
+ * with the cached KV vectors).  If k_new/v_new are given they are appended at slot lens[b,l] first
+ * and lens is incremented.  o = softmax_j(scale_l * q.Kc_j) . Vc over the lens slots.
+ * q [B,L,H,D], k_new/v_new [B,L,Hkv,D], out [B,L,H,D] (rounded to bf16 if out_bf16).
+ * Returns -1 if an append would exceed a segment's capacity (nothing is modified then).
+ * ------------------------------------------------------------------------------------------- */
+int pkvo_decode_attn(int B, int L, int H, int Hkv, int D, int l0, int l1, const float *q,
+                     const float *k_new, const float *v_new, const float *scale, float *kc,
+                     float *vc, const int64_t *seg_off, const int32_t *caps, int32_t *lens,
+                     float *out, int out_bf16) {
+    const int grp = H / Hkv;
+    if (k_new)
+        for (int b = 0; b < B; ++b)
+            for (int l = l0; l < l1; ++l)
+                if (lens[b * L + l] + 1 > caps[b * L + l]) return -1;
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+    for (int b = 0; b < B; ++b)
+        for (int l = l0; l < l1; ++l) {
+            const long bl = (long)b * L + l;
+            const int cap = caps[bl];
+            int len = lens[bl];
+            if (k_new) {
+                for (int h = 0; h < Hkv; ++h) {
+                    const size_t dst = ((size_t)seg_off[bl] * Hkv + (size_t)h * cap + len) * D;
+                    memcpy(kc + dst, k_new + ((size_t)bl * Hkv + h) * D, sizeof(float) * (size_t)D);
+                    memcpy(vc + dst, v_new + ((size_t)bl * Hkv + h) * D, sizeof(float) * (size_t)D);
+                }
+                len += 1;
+                lens[bl] = len;
+            }
+            double *s = (double *)malloc(sizeof(double) * (size_t)(len > 0 ? len : 1));
+            for (int h = 0; h < H; ++h) {
+                const float *qh = q + ((size_t)bl * H + h) * D;
+                const size_t base = ((size_t)seg_off[bl] * Hkv + (size_t)(h / grp) * cap) * D;
+                float *oh = out + ((size_t)bl * H + h) * D;
+                if (len == 0) { /* empty cache: defined as a zero output */
+                    for (int d = 0; d < D; ++d) oh[d] = 0.0f;
+                    continue;
+                }
+                double mx = -INFINITY;
+                for (int j = 0; j < len; ++j) {
+                    double dot = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        dot += (double)qh[d] * (double)kc[base + (size_t)j * D + d];
+                    s[j] = (double)scale[l] * dot;
+                    if (s[j] > mx) mx = s[j];
+                }
+                double den = 0.0;
+                for (int j = 0; j < len; ++j) { s[j] = exp(s[j] - mx); den += s[j]; }
+                for (int d = 0; d < D; ++d) {
+                    double acc = 0.0;
+                    for (int j = 0; j < len; ++j)
+                        acc += s[j] * (double)vc[base + (size_t)j * D + d];
+                    acc /= den;
+                    oh[d] = out_bf16 ? pkvo_round_bf16(acc) : (float)acc;
+                }
+            }
+            free(s);
+        }
+    return 0;
+}
