@@ -1,0 +1,159 @@
+/*
+ * prefixkv.h -- C ABI of the MI355X (gfx950) PrefixKV hot-path library.
+ *
+ * PrefixKV (arXiv 2412.03409) compresses the KV cache of a decoder after prefill: every cached
+ * position of layer l gets an importance (Sec. 3.2), positions are ranked per layer, and ONE
+ * retention ratio p, found by the binary search of Algorithm 1 (Sec. 3.3, Eq. 1), decides how long
+ * a prefix of each layer's ranking is kept so that all layers together meet a KV budget.
+ *
+ * General rules for every entry point
+ *   - Pointers marked [dev] are device (HBM) memory OWNED BY THE CALLER; [host] are host memory.
+ *     The library never allocates, frees or synchronises.  All work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and may still be running when the
+ *     call returns.  Scratch space comes from the caller: `ws` [dev], `ws_bytes` >= the value of
+ *     prefixkv_workspace_bytes() for the same arguments; its contents are undefined afterwards.
+ *   - The return value reports ARGUMENT errors synchronously (pkv_status); nothing is enqueued
+ *     when it is non-zero.  Data-dependent problems are reported through device status words.
+ *   - Layouts are row-major with the head dimension D contiguous.  Where strides are given they
+ *     are in ELEMENTS.  D is 64 or 128, H % Hkv == 0, 1 <= L <= 64, 1 <= N <= 8192, B >= 1.
+ *   - Calls that use the same workspace or the same output buffers must be ordered by the
+ *     caller (same stream, or events).  There is no global state.
+ */
+#ifndef PREFIXKV_H
+#define PREFIXKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PKV_OK = 0,
+    PKV_ERR_NULL = 1,        /* a required pointer is NULL */
+    PKV_ERR_DIM = 2,         /* a dimension is out of the supported range */
+    PKV_ERR_DTYPE = 3,       /* unknown dtype */
+    PKV_ERR_STRIDE = 4,      /* stride not a multiple of 8 elements (16-byte rows needed) or negative */
+    PKV_ERR_WORKSPACE = 5,   /* ws is NULL or ws_bytes too small */
+    PKV_ERR_BUDGET = 6,      /* budget_tokens < 1, tol_tokens < 0 or max_iters < 1 */
+    PKV_ERR_UNSUPPORTED = 7, /* valid request this build has no kernel for */
+    PKV_ERR_HIP = 8          /* a launch failed; see hipGetLastError */
+} pkv_status;
+
+/* bits of the per-sequence device status word written by prefixkv_select */
+enum {
+    PKV_DEV_NONFINITE = 1,  /* importance holds NaN or Inf */
+    PKV_DEV_NEGATIVE = 2,   /* importance holds a negative value (-0.0 is accepted as 0) */
+    PKV_DEV_ZERO_LAYER = 4, /* some layer's fixed-point weights are all zero */
+    PKV_DEV_RANGE = 8       /* a layer's importance sums to more than 2^17 */
+};
+
+typedef enum { PKV_F32 = 0, PKV_BF16 = 1 } pkv_dtype;
+
+/* B sequences, L layers, H query heads, Hkv key/value heads, N prompt positions, head dim D;
+ * dtype is the storage type of Q/K/V, of the compressed cache and of the attention output. */
+typedef struct { int32_t B, L, H, Hkv, N, D; int32_t dtype; } pkv_shape;
+
+/* Element strides of a [B, L, heads, N, D] tensor (D-stride is 1). */
+typedef struct { int64_t b, l, h, n; } pkv_strides;
+
+typedef void *pkv_stream; /* hipStream_t */
+
+int prefixkv_version(void);
+const char *prefixkv_status_string(int status);
+
+/* Workspace bytes for op = PKV_OP_*.  `cache_tokens` is only used by PKV_OP_DECODE (the number of
+ * token slots allocated in kc/vc); pass 0 otherwise.  `has_lse` (PKV_OP_IMPORTANCE) = the caller
+ * will pass its own lse.  Returns 0 for invalid arguments. */
+enum { PKV_OP_IMPORTANCE = 0, PKV_OP_SELECT = 1, PKV_OP_COMPACT = 2, PKV_OP_DECODE = 3 };
+size_t prefixkv_workspace_bytes(int op, const pkv_shape *shape, int64_t cache_tokens, int has_lse);
+
+/* ---- Stage 1: KV importance (Sec. 3.2, the causal score matrix a_l^{i,m,n} and the importance
+ * metric I_l^n = Average_i(sum_m a_l^{i,m,n})).
+ *   importance[b,l,n] = (1/H) * sum_h sum_{m>=n} softmax_{j<=m}(scale[l] * q[b,l,h,m,:].k[b,l,g(h),j,:])[n]
+ * with g(h) = h / (H/Hkv).  The paper's formula has no logit scale (scale = 1); a model passes its
+ * own, usually 1/sqrt(D).
+ *   q [dev] [B,L,H,N,D] with strides qs;  k [dev] [B,L,Hkv,N,D] with strides ks  (shape->dtype)
+ *   scale [dev] fp32 [L]
+ *   lse [dev] fp32 [B,L,H,N] = log sum_{j<=m} exp(scale*q_m.k_j) of every causal row if the caller
+ *       already has it from its prefill attention, or NULL: it is then computed here (second pass).
+ *   importance [dev] fp32 [B,L,N], out (dense).
+ * bf16 inputs use bf16 MFMA with fp32 accumulation; exp and all sums are fp32. */
+int prefixkv_importance(const pkv_shape *shape, const void *q, pkv_strides qs, const void *k,
+                        pkv_strides ks, const float *scale, const float *lse, float *importance,
+                        void *ws, size_t ws_bytes, pkv_stream stream);
+
+/* ---- Stages 2+3: priority sequences, cumulative priority and the global search (Sec. 3.2 for
+ * the normalised, sorted, cumulated importance P_l^o; Sec. 3.3, Eq. 1 and Algorithm 1 for p).
+ * Per sequence b and layer l:
+ *   order[b,l,:]  positions sorted by importance descending, equal values by ascending position
+ *   cum[b,l,k-1]  C_k = sum of the first k sorted fixed-point weights, weight = floor(imp * 2^36)
+ *                 (exact integers; the cumulative priority of a prefix of k is C_k / C_N)
+ *   prefix        (float)(C_k / C_N), informational, may be NULL
+ * Per sequence b: Algorithm 1 on p in [0,1]; the prefix length of layer l at p is the smallest
+ * k >= 1 with C_k >= p*C_N (p*C_N is one fp64 product), p >= 1 keeps N.  Each iteration evaluates
+ * the midpoint and stops when |sum_l k_l - budget_tokens| <= tol_tokens, after max_iters
+ * evaluations, or when the midpoint no longer differs from an end of the interval.
+ *   budget_tokens <= L   -> all lengths 1, p = 0, iters = 0;
+ *   budget_tokens >= L*N -> all lengths N, p = 1, iters = 0 (budget of 100%: no compression).
+ * If fixup != 0 and the total missed the budget, the configuration is rescaled proportionally
+ * (Sec. 3.3, last sentence of "Binary search for optimal configuration"): k_l*budget/total rounded
+ * down and clamped to [1,N], then the remaining tokens are handed out one per layer in order of
+ * largest remainder (ties: lower layer), cyclically, so that sum_l lengths == budget_tokens.
+ *   lengths [B,L] i32, p_out [B] f64 (last evaluated midpoint), iters [B] i32 (evaluated
+ *   midpoints), raw_total [B] i64 (sum of lengths before the rescale), status [B] i32
+ *   (PKV_DEV_* bits; if non-zero the sequence gets lengths = 0, p = 0, iters = 0, raw_total = 0
+ *   and its order/cum/prefix contents are unspecified).  All outputs [dev]. */
+typedef struct {
+    int64_t budget_tokens; /* per sequence */
+    int64_t tol_tokens;    /* >= 0 */
+    int32_t max_iters;     /* >= 1; 64 always reaches the stopping interval */
+    int32_t fixup;         /* 0 / 1 */
+} pkv_select_params;
+
+int prefixkv_select(int B, int L, int N, const float *importance /* [dev] [B,L,N] */,
+                    const pkv_select_params *params /* [host] */, int32_t *order, uint64_t *cum,
+                    float *prefix, int32_t *lengths, double *p_out, int32_t *iters,
+                    int64_t *raw_total, int32_t *status, void *ws, size_t ws_bytes,
+                    pkv_stream stream);
+
+/* ---- Stage 4a: compaction (Sec. 3.2: the top R_l proportion of KV vectors is retained in each
+ * head of layer l; Fig. 3(a): layer-wise compressed cache).
+ * The kept set of (b,l) is order[b,l,0..lengths[b,l]); it is stored in ascending position.
+ * Ragged layout, computed on the device: caps[b,l] = lengths[b,l] + decode_capacity,
+ * seg_off[b,l] = exclusive prefix sum of caps in (b,l) order (in tokens); segment (b,l) of kc/vc
+ * is the [Hkv][caps][D] block starting at element seg_off*Hkv*D; kept_pos uses the same token
+ * offsets (one int per slot).  lens[b,l] = lengths[b,l] = the number of occupied slots.
+ * kc, vc must hold at least prefixkv_cache_tokens_upper_bound() tokens * Hkv * D elements and
+ * kept_pos that many ints.  Slots beyond lens are not written.
+ *   k, v [dev] [B,L,Hkv,N,D] with strides; order [dev] [B,L,N]; lengths [dev] [B,L]
+ *   seg_off [dev] i64 [B,L], caps [dev] i32 [B,L], lens [dev] i32 [B,L]: out */
+int prefixkv_compact(const pkv_shape *shape, const void *k, pkv_strides ks, const void *v,
+                     pkv_strides vs, const int32_t *order, const int32_t *lengths,
+                     int decode_capacity, int64_t *seg_off, int32_t *caps, void *kc, void *vc,
+                     int32_t *kept_pos, int32_t *lens, void *ws, size_t ws_bytes,
+                     pkv_stream stream);
+
+/* Tokens to allocate for kc/vc/kept_pos when every sequence keeps at most `budget_tokens`. */
+int64_t prefixkv_cache_tokens_upper_bound(int B, int64_t budget_tokens, int L, int decode_capacity);
+
+/* ---- Stage 4b: one decode step over layers [l0,l1) (Sec. 3.1: the newest token's query
+ * interacts with the cached KV vectors).
+ * If k_new/v_new are non-NULL, the new token's key/value of every (b,l,kv head) are first stored
+ * in slot lens[b,l] of the segment and lens[b,l] becomes lens[b,l]+1 (the caller guarantees
+ * lens < caps; a full segment drops the append and the step attends over the old slots).  Then
+ *   out[b,l,h,:] = sum_j softmax_j(scale[l] * q[b,l,h,:].kc_j) * vc_j   over the lens slots of kv
+ * head g(h); an empty segment gives zeros.  fp32 softmax and accumulation; out in shape->dtype.
+ *   q, out [dev] [B,L,H,D] dense;  k_new, v_new [dev] [B,L,Hkv,D] dense or NULL (both)
+ *   kc, vc, seg_off, caps as produced by prefixkv_compact;  lens [dev] in/out
+ *   cache_tokens = token slots allocated in kc/vc (>= sum of caps); sizes the workspace. */
+int prefixkv_decode_attn(const pkv_shape *shape, int l0, int l1, const void *q, const void *k_new,
+                         const void *v_new, const float *scale, void *kc, void *vc,
+                         const int64_t *seg_off, const int32_t *caps, int32_t *lens, void *out,
+                         int64_t cache_tokens, void *ws, size_t ws_bytes, pkv_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PREFIXKV_H */

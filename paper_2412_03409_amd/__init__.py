@@ -1,0 +1,12 @@
+"""MI355X-native PrefixKV hot path: thin Python binding over the C-ABI library libprefixkv.so.
+
+Every step (importance, sort + cumulative priority, the search for the retention ratio p,
+compaction, decode attention) runs in hand-written HIP kernels; this package only marshals
+arguments.  PyTorch is used for device memory and streams.  There is no CPU fallback: importing
+the binding without the built library raises.
+"""
+from .binding import (  # noqa: F401
+    DecodeState, PKV_BF16, PKV_F32, PrefixKVError, SelectResult, CompactResult, lib_path, load,
+    prefixkv_cache_tokens_upper_bound, prefixkv_compact, prefixkv_decode_attn, prefixkv_importance,
+    prefixkv_select, prefixkv_status_string, prefixkv_version, prefixkv_workspace_bytes,
+)

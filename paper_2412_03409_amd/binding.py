@@ -1,0 +1,292 @@
+"""ctypes binding of include/prefixkv.h.  Argument marshalling only.
+
+The wrappers have the names of the C entry points.  Tensors must live on the GPU; outputs and the
+workspace are allocated here with torch (the library itself never allocates) unless passed in.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import dataclass
+from pathlib import Path
+from typing import Optional
+
+import torch
+
+_HERE = Path(__file__).resolve().parent
+_LIB_PATH = _HERE / "libprefixkv.so"
+
+PKV_F32, PKV_BF16 = 0, 1
+OP_IMPORTANCE, OP_SELECT, OP_COMPACT, OP_DECODE = 0, 1, 2, 3
+
+
+class PrefixKVError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: status {code} ({prefixkv_status_string(code)})")
+        self.code = code
+
+
+class _Shape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "L", "H", "Hkv", "N", "D", "dtype")]
+
+
+class _Strides(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("b", "l", "h", "n")]
+
+
+class _SelectParams(C.Structure):
+    _fields_ = [("budget_tokens", C.c_int64), ("tol_tokens", C.c_int64), ("max_iters", C.c_int32),
+                ("fixup", C.c_int32)]
+
+
+_lib = None
+
+
+def lib_path() -> Path:
+    return _LIB_PATH
+
+
+def load() -> C.CDLL:
+    """Load libprefixkv.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _LIB_PATH.exists():
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2412_03409_amd.build` "
+                          "(hipcc, gfx950); there is no CPU path")
+    L = C.CDLL(str(_LIB_PATH))
+    vp, i32, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+    L.prefixkv_version.restype = C.c_int
+    L.prefixkv_status_string.restype = C.c_char_p
+    L.prefixkv_status_string.argtypes = [C.c_int]
+    L.prefixkv_workspace_bytes.restype = sz
+    L.prefixkv_workspace_bytes.argtypes = [i32, C.POINTER(_Shape), i64, i32]
+    L.prefixkv_importance.restype = C.c_int
+    L.prefixkv_importance.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, vp, vp, sz, vp]
+    L.prefixkv_select.restype = C.c_int
+    L.prefixkv_select.argtypes = [i32, i32, i32, vp, C.POINTER(_SelectParams), vp, vp, vp, vp, vp, vp, vp,
+                                  vp, vp, sz, vp]
+    L.prefixkv_compact.restype = C.c_int
+    L.prefixkv_compact.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, i32, vp, vp, vp,
+                                   vp, vp, vp, vp, sz, vp]
+    L.prefixkv_cache_tokens_upper_bound.restype = i64
+    L.prefixkv_cache_tokens_upper_bound.argtypes = [i32, i64, i32, i32]
+    L.prefixkv_decode_attn.restype = C.c_int
+    L.prefixkv_decode_attn.argtypes = [C.POINTER(_Shape), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                       i64, vp, sz, vp]
+    _lib = L
+    return L
+
+
+def prefixkv_version() -> int:
+    return int(load().prefixkv_version())
+
+
+def prefixkv_status_string(code: int) -> str:
+    return load().prefixkv_status_string(int(code)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return PKV_F32
+    if t.dtype == torch.bfloat16:
+        return PKV_BF16
+    raise TypeError(f"unsupported storage dtype {t.dtype}")
+
+
+def _shape(B, L, H, Hkv, N, D, dtype) -> _Shape:
+    return _Shape(B, L, H, Hkv, N, D, dtype)
+
+
+def _strides5(t: torch.Tensor) -> _Strides:
+    if t.stride(4) != 1:
+        raise ValueError("the head dimension must be contiguous")
+    return _Strides(t.stride(0), t.stride(1), t.stride(2), t.stride(3))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _need_cuda(*ts):
+    for t in ts:
+        if t is not None and not t.is_cuda:
+            raise ValueError("all tensors must be on the GPU")
+
+
+def _ws(nbytes: int, device, ws: Optional[torch.Tensor]) -> torch.Tensor:
+    if ws is not None:
+        if ws.numel() * ws.element_size() < nbytes:
+            raise ValueError("workspace too small")
+        return ws
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def prefixkv_workspace_bytes(op: int, B, L, H, Hkv, N, D, dtype, cache_tokens: int = 0,
+                             has_lse: bool = False) -> int:
+    s = _shape(B, L, H, Hkv, N, D, dtype)
+    return int(load().prefixkv_workspace_bytes(op, C.byref(s), cache_tokens, int(has_lse)))
+
+
+def prefixkv_cache_tokens_upper_bound(B: int, budget_tokens: int, L: int, decode_capacity: int) -> int:
+    return int(load().prefixkv_cache_tokens_upper_bound(B, budget_tokens, L, decode_capacity))
+
+
+def prefixkv_importance(q: torch.Tensor, k: torch.Tensor, scale: torch.Tensor,
+                        lse: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                        ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """q [B,L,H,N,D], k [B,L,Hkv,N,D] (bf16 or f32), scale [L] f32, optional lse [B,L,H,N] f32
+    -> importance [B,L,N] f32."""
+    _need_cuda(q, k, scale, lse, out, ws)
+    B, L, H, N, D = q.shape
+    Hkv = k.shape[2]
+    if k.shape != (B, L, Hkv, N, D) or k.dtype != q.dtype:
+        raise ValueError("k must be [B,L,Hkv,N,D] with q's dtype")
+    if scale.dtype != torch.float32 or scale.shape != (L,) or not scale.is_contiguous():
+        raise ValueError("scale must be contiguous f32 [L]")
+    if lse is not None and (lse.dtype != torch.float32 or lse.shape != (B, L, H, N) or not lse.is_contiguous()):
+        raise ValueError("lse must be contiguous f32 [B,L,H,N]")
+    s = _shape(B, L, H, Hkv, N, D, _dtype_code(q))
+    if out is None:
+        out = torch.empty((B, L, N), dtype=torch.float32, device=q.device)
+    nbytes = load().prefixkv_workspace_bytes(OP_IMPORTANCE, C.byref(s), 0, int(lse is not None))
+    w = _ws(nbytes, q.device, ws)
+    rc = load().prefixkv_importance(C.byref(s), _ptr(q), _strides5(q), _ptr(k), _strides5(k), _ptr(scale),
+                                    _ptr(lse), _ptr(out), _ptr(w), w.numel() * w.element_size(), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_importance")
+    return out
+
+
+@dataclass
+class SelectResult:
+    order: torch.Tensor      # [B,L,N] i32
+    cum: torch.Tensor        # [B,L,N] i64 holding the u64 bit pattern
+    prefix: Optional[torch.Tensor]  # [B,L,N] f32
+    lengths: torch.Tensor    # [B,L] i32
+    p: torch.Tensor          # [B] f64
+    iters: torch.Tensor      # [B] i32
+    raw_total: torch.Tensor  # [B] i64
+    status: torch.Tensor     # [B] i32
+
+
+def prefixkv_select(importance: torch.Tensor, budget_tokens: int, tol_tokens: int = 0,
+                    max_iters: int = 64, fixup: bool = True, want_prefix: bool = True,
+                    out: Optional[SelectResult] = None, ws: Optional[torch.Tensor] = None) -> SelectResult:
+    """importance [B,L,N] f32 -> SelectResult (all on the device; nothing is read back)."""
+    _need_cuda(importance, ws)
+    if importance.dtype != torch.float32 or importance.dim() != 3 or not importance.is_contiguous():
+        raise ValueError("importance must be contiguous f32 [B,L,N]")
+    B, L, N = importance.shape
+    dev = importance.device
+    if out is None:
+        out = SelectResult(
+            order=torch.empty((B, L, N), dtype=torch.int32, device=dev),
+            cum=torch.empty((B, L, N), dtype=torch.int64, device=dev),
+            prefix=torch.empty((B, L, N), dtype=torch.float32, device=dev) if want_prefix else None,
+            lengths=torch.empty((B, L), dtype=torch.int32, device=dev),
+            p=torch.empty(B, dtype=torch.float64, device=dev),
+            iters=torch.empty(B, dtype=torch.int32, device=dev),
+            raw_total=torch.empty(B, dtype=torch.int64, device=dev),
+            status=torch.empty(B, dtype=torch.int32, device=dev))
+    prm = _SelectParams(int(budget_tokens), int(tol_tokens), int(max_iters), int(bool(fixup)))
+    w = _ws(B * L * 4, dev, ws)
+    rc = load().prefixkv_select(B, L, N, _ptr(importance), C.byref(prm), _ptr(out.order), _ptr(out.cum),
+                                _ptr(out.prefix), _ptr(out.lengths), _ptr(out.p), _ptr(out.iters),
+                                _ptr(out.raw_total), _ptr(out.status), _ptr(w),
+                                w.numel() * w.element_size(), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_select")
+    return out
+
+
+@dataclass
+class CompactResult:
+    kc: torch.Tensor         # flat [cache_tokens*Hkv*D] storage dtype
+    vc: torch.Tensor
+    kept_pos: torch.Tensor   # [cache_tokens] i32
+    seg_off: torch.Tensor    # [B,L] i64 (tokens)
+    caps: torch.Tensor       # [B,L] i32
+    lens: torch.Tensor       # [B,L] i32
+    cache_tokens: int
+    Hkv: int
+    D: int
+
+
+def prefixkv_compact(k: torch.Tensor, v: torch.Tensor, order: torch.Tensor, lengths: torch.Tensor,
+                     decode_capacity: int, cache_tokens: int,
+                     out: Optional[CompactResult] = None) -> CompactResult:
+    """k,v [B,L,Hkv,N,D]; order [B,L,N] i32; lengths [B,L] i32 -> ragged compressed cache.
+    cache_tokens: token slots to allocate (prefixkv_cache_tokens_upper_bound)."""
+    _need_cuda(k, v, order, lengths)
+    B, L, Hkv, N, D = k.shape
+    if v.shape != k.shape or v.dtype != k.dtype:
+        raise ValueError("v must match k")
+    if order.dtype != torch.int32 or order.shape != (B, L, N) or not order.is_contiguous():
+        raise ValueError("order must be contiguous i32 [B,L,N]")
+    if lengths.dtype != torch.int32 or lengths.shape != (B, L) or not lengths.is_contiguous():
+        raise ValueError("lengths must be contiguous i32 [B,L]")
+    dev = k.device
+    if out is None:
+        out = CompactResult(
+            kc=torch.empty(cache_tokens * Hkv * D, dtype=k.dtype, device=dev),
+            vc=torch.empty(cache_tokens * Hkv * D, dtype=k.dtype, device=dev),
+            kept_pos=torch.empty(cache_tokens, dtype=torch.int32, device=dev),
+            seg_off=torch.empty((B, L), dtype=torch.int64, device=dev),
+            caps=torch.empty((B, L), dtype=torch.int32, device=dev),
+            lens=torch.empty((B, L), dtype=torch.int32, device=dev),
+            cache_tokens=int(cache_tokens), Hkv=Hkv, D=D)
+    s = _shape(B, L, Hkv, Hkv, N, D, _dtype_code(k))
+    rc = load().prefixkv_compact(C.byref(s), _ptr(k), _strides5(k), _ptr(v), _strides5(v), _ptr(order),
+                                 _ptr(lengths), int(decode_capacity), _ptr(out.seg_off), _ptr(out.caps),
+                                 _ptr(out.kc), _ptr(out.vc), _ptr(out.kept_pos), _ptr(out.lens), None, 0,
+                                 _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_compact")
+    return out
+
+
+@dataclass
+class DecodeState:
+    """Pre-sized workspace for prefixkv_decode_attn (reused across steps)."""
+    ws: torch.Tensor
+
+    @staticmethod
+    def create(cache: CompactResult, B: int, L: int, H: int, N: int) -> "DecodeState":
+        dt = PKV_F32 if cache.kc.dtype == torch.float32 else PKV_BF16
+        nbytes = prefixkv_workspace_bytes(OP_DECODE, B, L, H, cache.Hkv, N, cache.D, dt, cache.cache_tokens)
+        return DecodeState(torch.empty(max(nbytes, 256), dtype=torch.uint8, device=cache.kc.device))
+
+
+def prefixkv_decode_attn(cache: CompactResult, q: torch.Tensor, k_new: Optional[torch.Tensor],
+                         v_new: Optional[torch.Tensor], scale: torch.Tensor, N: int,
+                         l0: int = 0, l1: Optional[int] = None, out: Optional[torch.Tensor] = None,
+                         state: Optional[DecodeState] = None) -> torch.Tensor:
+    """One decode step over layers [l0,l1): q [B,L,H,D], k_new/v_new [B,L,Hkv,D] or None
+    -> out [B,L,H,D].  Appends in place and advances cache.lens on the device."""
+    _need_cuda(q, k_new, v_new, scale, out)
+    B, L, H, D = q.shape
+    l1 = L if l1 is None else l1
+    if not q.is_contiguous() or q.dtype != cache.kc.dtype or D != cache.D:
+        raise ValueError("q must be contiguous [B,L,H,D] in the cache dtype")
+    for t in (k_new, v_new):
+        if t is not None and (t.shape != (B, L, cache.Hkv, D) or not t.is_contiguous() or t.dtype != q.dtype):
+            raise ValueError("k_new/v_new must be contiguous [B,L,Hkv,D] in the cache dtype")
+    if scale.dtype != torch.float32 or scale.shape != (L,) or not scale.is_contiguous():
+        raise ValueError("scale must be contiguous f32 [L]")
+    if out is None:
+        out = torch.empty((B, L, H, D), dtype=q.dtype, device=q.device)
+    if state is None:
+        state = DecodeState.create(cache, B, L, H, N)
+    s = _shape(B, L, H, cache.Hkv, N, D, _dtype_code(q))
+    w = state.ws
+    rc = load().prefixkv_decode_attn(C.byref(s), int(l0), int(l1), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                     _ptr(scale), _ptr(cache.kc), _ptr(cache.vc), _ptr(cache.seg_off),
+                                     _ptr(cache.caps), _ptr(cache.lens), _ptr(out), int(cache.cache_tokens),
+                                     _ptr(w), w.numel() * w.element_size(), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_decode_attn")
+    return out

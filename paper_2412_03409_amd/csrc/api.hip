@@ -1,0 +1,126 @@
+// C ABI of libprefixkv: argument validation and dispatch.  No allocation, no synchronisation, no
+// global state; every launch goes to the caller's stream.
+#include "pkv_common.hpp"
+
+using namespace pkv;
+
+namespace {
+
+bool shape_ok(const pkv_shape* s) {
+    return s->B >= 1 && s->L >= 1 && s->L <= kMaxL && s->H >= 1 && s->Hkv >= 1 && s->H % s->Hkv == 0 &&
+           s->N >= 1 && s->N <= kMaxN && (s->D == 64 || s->D == 128);
+}
+bool dtype_ok(const pkv_shape* s) { return s->dtype == PKV_F32 || s->dtype == PKV_BF16; }
+// rows are moved in 16-byte pieces
+bool strides_ok(const pkv_strides& t, int esize) {
+    const int64_t a = 16 / esize;
+    return t.b >= 0 && t.l >= 0 && t.h >= 0 && t.n > 0 && t.b % a == 0 && t.l % a == 0 && t.h % a == 0 &&
+           t.n % a == 0;
+}
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+int prefixkv_version(void) { return 100; }
+
+const char* prefixkv_status_string(int status) {
+    switch (status) {
+        case PKV_OK: return "ok";
+        case PKV_ERR_NULL: return "required pointer is NULL";
+        case PKV_ERR_DIM: return "dimension out of range";
+        case PKV_ERR_DTYPE: return "unknown dtype";
+        case PKV_ERR_STRIDE: return "stride or pointer not 16-byte aligned";
+        case PKV_ERR_WORKSPACE: return "workspace missing or too small";
+        case PKV_ERR_BUDGET: return "invalid budget, tolerance or iteration limit";
+        case PKV_ERR_UNSUPPORTED: return "unsupported configuration";
+        case PKV_ERR_HIP: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+size_t prefixkv_workspace_bytes(int op, const pkv_shape* s, int64_t cache_tokens, int has_lse) {
+    if (!s || !shape_ok(s) || !dtype_ok(s)) return 0;
+    switch (op) {
+        case PKV_OP_IMPORTANCE: return importance_ws_bytes(*s, has_lse != 0);
+        case PKV_OP_SELECT: return select_ws_bytes(s->B, s->L, s->N);
+        case PKV_OP_COMPACT: return compact_ws_bytes(*s) + 256;
+        case PKV_OP_DECODE: return cache_tokens < 0 ? 0 : decode_ws_bytes(*s, cache_tokens);
+        default: return 0;
+    }
+}
+
+int prefixkv_importance(const pkv_shape* s, const void* q, pkv_strides qs, const void* k, pkv_strides ks,
+                        const float* scale, const float* lse, float* importance, void* ws,
+                        size_t ws_bytes, pkv_stream stream) {
+    if (!s || !q || !k || !scale || !importance) return PKV_ERR_NULL;
+    if (!shape_ok(s)) return PKV_ERR_DIM;
+    if (!dtype_ok(s)) return PKV_ERR_DTYPE;
+    const int esize = s->dtype == PKV_F32 ? 4 : 2;
+    if (!strides_ok(qs, esize) || !strides_ok(ks, esize) || !aligned16(q) || !aligned16(k))
+        return PKV_ERR_STRIDE;
+    if (!ws || ws_bytes < importance_ws_bytes(*s, lse != nullptr)) return PKV_ERR_WORKSPACE;
+    const hipError_t e = launch_importance(*s, q, to_strides(qs), k, to_strides(ks), scale, lse, importance,
+                                           ws, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int prefixkv_select(int B, int L, int N, const float* importance, const pkv_select_params* params,
+                    int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
+                    int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, size_t ws_bytes,
+                    pkv_stream stream) {
+    if (!importance || !params || !order || !cum || !lengths || !p_out || !iters || !raw_total || !status)
+        return PKV_ERR_NULL;
+    if (B < 1 || L < 1 || L > kMaxL || N < 1 || N > kMaxN) return PKV_ERR_DIM;
+    if (params->budget_tokens < 1 || params->tol_tokens < 0 || params->max_iters < 1) return PKV_ERR_BUDGET;
+    if (!ws || ws_bytes < select_ws_bytes(B, L, N)) return PKV_ERR_WORKSPACE;
+    const hipError_t e = launch_select(B, L, N, importance, *params, order, cum, prefix, lengths, p_out,
+                                       iters, raw_total, status, ws, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int prefixkv_compact(const pkv_shape* s, const void* k, pkv_strides ks, const void* v, pkv_strides vs,
+                     const int32_t* order, const int32_t* lengths, int decode_capacity, int64_t* seg_off,
+                     int32_t* caps, void* kc, void* vc, int32_t* kept_pos, int32_t* lens, void* ws,
+                     size_t ws_bytes, pkv_stream stream) {
+    if (!s || !k || !v || !order || !lengths || !seg_off || !caps || !kc || !vc || !kept_pos || !lens)
+        return PKV_ERR_NULL;
+    if (!shape_ok(s) || decode_capacity < 0) return PKV_ERR_DIM;
+    if (!dtype_ok(s)) return PKV_ERR_DTYPE;
+    const int esize = s->dtype == PKV_F32 ? 4 : 2;
+    if (!strides_ok(ks, esize) || !strides_ok(vs, esize) || !aligned16(k) || !aligned16(v) ||
+        !aligned16(kc) || !aligned16(vc))
+        return PKV_ERR_STRIDE;
+    if ((size_t)((s->N + 63) / 64) * s->Hkv * s->B * s->L > 0x7fffffffull) return PKV_ERR_UNSUPPORTED;
+    (void)ws; (void)ws_bytes;  // this stage needs no scratch
+    const hipError_t e = launch_compact(*s, k, to_strides(ks), v, to_strides(vs), order, lengths,
+                                        decode_capacity, seg_off, caps, kc, vc, kept_pos, lens, ws,
+                                        (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int64_t prefixkv_cache_tokens_upper_bound(int B, int64_t budget_tokens, int L, int decode_capacity) {
+    if (B < 1 || L < 1 || budget_tokens < 0 || decode_capacity < 0) return 0;
+    return (int64_t)B * (budget_tokens + (int64_t)L * decode_capacity);
+}
+
+int prefixkv_decode_attn(const pkv_shape* s, int l0, int l1, const void* q, const void* k_new,
+                         const void* v_new, const float* scale, void* kc, void* vc, const int64_t* seg_off,
+                         const int32_t* caps, int32_t* lens, void* out, int64_t cache_tokens, void* ws,
+                         size_t ws_bytes, pkv_stream stream) {
+    if (!s || !q || !scale || !kc || !vc || !seg_off || !caps || !lens || !out) return PKV_ERR_NULL;
+    if ((k_new == nullptr) != (v_new == nullptr)) return PKV_ERR_NULL;
+    if (!shape_ok(s) || l0 < 0 || l1 > s->L || l0 >= l1 || cache_tokens < 0) return PKV_ERR_DIM;
+    if (!dtype_ok(s)) return PKV_ERR_DTYPE;
+    if (!aligned16(q) || !aligned16(kc) || !aligned16(vc) || !aligned16(out) || !aligned16(k_new) ||
+        !aligned16(v_new))
+        return PKV_ERR_STRIDE;
+    if ((int64_t)s->B * (l1 - l0) > 8192) return PKV_ERR_UNSUPPORTED;  // unit table lives in LDS
+    if (!ws || ws_bytes < decode_ws_bytes(*s, cache_tokens)) return PKV_ERR_WORKSPACE;
+    const hipError_t e = launch_decode(*s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, lens, out,
+                                       cache_tokens, ws, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+}  // extern "C"

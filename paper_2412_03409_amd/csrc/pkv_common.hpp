@@ -1,0 +1,61 @@
+// Shared declarations of the HIP side of libprefixkv: launcher prototypes (one per stage, defined
+// next to their kernels) and a few device helpers.  gfx950 only, wave64.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/prefixkv.h"
+
+namespace pkv {
+
+constexpr int kWave = 64;
+constexpr int kMaxL = 64;
+constexpr int kMaxN = 8192;
+constexpr int kDecodeChunk = 64;   // tokens of one (b,l,kv-head) segment handled by one wave
+constexpr int kXcds = 8;           // L2 slices (XCDs) of the chip; workgroup id % 8 picks the XCD
+
+typedef unsigned short bf16_t;     // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+// Consecutive workgroup ids land on different XCDs; map them so that `nblk/8` consecutive logical
+// ids share an XCD (and its L2).  nblk must be a multiple of 8.
+__device__ __forceinline__ uint32_t xcd_swizzle(uint32_t bid, uint32_t nblk) {
+    return (bid % kXcds) * (nblk / kXcds) + bid / kXcds;
+}
+
+struct Strides { int64_t b, l, h, n; };
+inline Strides to_strides(pkv_strides s) { return Strides{s.b, s.l, s.h, s.n}; }
+
+// ---- launchers (return hipError_t of the launches) -------------------------------------------------
+size_t importance_ws_bytes(const pkv_shape& s, bool has_lse);
+hipError_t launch_importance(const pkv_shape& s, const void* q, Strides qs, const void* k, Strides ks,
+                             const float* scale, const float* lse, float* importance, void* ws,
+                             hipStream_t st);
+
+size_t select_ws_bytes(int B, int L, int N);
+hipError_t launch_select(int B, int L, int N, const float* importance, const pkv_select_params& p,
+                         int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
+                         int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, hipStream_t st);
+
+size_t compact_ws_bytes(const pkv_shape& s);
+hipError_t launch_compact(const pkv_shape& s, const void* k, Strides ks, const void* v, Strides vs,
+                          const int32_t* order, const int32_t* lengths, int decode_capacity,
+                          int64_t* seg_off, int32_t* caps, void* kc, void* vc, int32_t* kept_pos,
+                          int32_t* lens, void* ws, hipStream_t st);
+
+size_t decode_ws_bytes(const pkv_shape& s, int64_t cache_tokens);
+hipError_t launch_decode(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
+                         const void* v_new, const float* scale, void* kc, void* vc,
+                         const int64_t* seg_off, const int32_t* caps, int32_t* lens, void* out,
+                         int64_t cache_tokens, void* ws, hipStream_t st);
+
+}  // namespace pkv

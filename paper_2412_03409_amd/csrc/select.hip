@@ -1,0 +1,272 @@
+// Stages 2 and 3 of the PrefixKV hot path.
+//
+//  sort_prefix_kernel  one workgroup per (sequence, layer): the priority sequence of Sec. 3.2 (positions
+//                      by importance, descending) by a bitonic sort of 64-bit keys held in LDS, then the
+//                      cumulative priority as an exact integer scan of fixed-point weights.
+//  search_kernel       one wavefront per sequence, one lane per layer: Algorithm 1 (Sec. 3.3) runs to
+//                      completion on the device, followed by the proportional rescale to the budget.
+//
+// Everything that decides an index or a length is integer or a single fp64 product + compare, so the
+// results do not depend on scan order or launch shape.
+#include "pkv_common.hpp"
+
+namespace pkv {
+
+__device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src) {
+    uint32_t lo = __shfl((uint32_t)v, src, kWave);
+    uint32_t hi = __shfl((uint32_t)(v >> 32), src, kWave);
+    return ((uint64_t)hi << 32) | lo;
+}
+// Sums never wrap: they stick at 2^62, far above the 2^53 limit that raises PKV_DEV_RANGE.
+__device__ __forceinline__ uint64_t sat_add(uint64_t a, uint64_t b) {
+    const uint64_t s = a + b, cap = 1ull << 62;
+    return s > cap ? cap : s;
+}
+__device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int d) {
+    uint32_t lo = __shfl_up((uint32_t)v, d, kWave);
+    uint32_t hi = __shfl_up((uint32_t)(v >> 32), d, kWave);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Sort key: high word = ~bits(importance) (non-negative floats order like their bit patterns, so the
+// complement orders them descending), low word = position (ascending among equal values).
+// Padding keys are all ones: they sort last and decode to weight 0.
+__global__ void sort_prefix_kernel(int N, int P, const float* __restrict__ importance,
+                                   int32_t* __restrict__ order, uint64_t* __restrict__ cum,
+                                   float* __restrict__ prefix, int32_t* __restrict__ seg_status) {
+    extern __shared__ uint64_t skey[];          // P keys, then reused for the scan
+    __shared__ uint64_t wave_tot[16];
+    __shared__ int s_flags;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const size_t seg = blockIdx.x;
+    const float* imp = importance + seg * (size_t)N;
+    if (tid == 0) s_flags = 0;
+    __syncthreads();
+
+    int flags = 0;
+    for (int i = tid; i < P; i += nt) {
+        uint64_t key = ~0ull;
+        if (i < N) {
+            uint32_t bits = __float_as_uint(imp[i]);
+            if ((bits & 0x7f800000u) == 0x7f800000u) flags |= PKV_DEV_NONFINITE;
+            else if (bits == 0x80000000u) bits = 0;  // -0.0 counts as +0.0
+            else if (bits & 0x80000000u) flags |= PKV_DEV_NEGATIVE;
+            key = ((uint64_t)(~bits) << 32) | (uint32_t)i;
+        }
+        skey[i] = key;
+    }
+    if (flags) atomicOr(&s_flags, flags);
+    __syncthreads();
+
+    // bitonic network, ascending
+    for (int k = 2; k <= P; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = tid; t < (P >> 1); t += nt) {
+                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                const int x = i | j;
+                const uint64_t a = skey[i], b = skey[x];
+                const bool up = (i & k) == 0;
+                if ((a > b) == up) { skey[i] = b; skey[x] = a; }
+            }
+            __syncthreads();
+        }
+    }
+
+    // fixed-point weights and their inclusive scan; each thread owns E consecutive sorted entries
+    const int E = P / nt;  // P and nt are powers of two with P >= nt
+    const int base = tid * E;
+    uint64_t local = 0;
+    const double two36 = 68719476736.0;
+    for (int e = 0; e < E; ++e) {
+        const uint64_t key = skey[base + e];
+        const float v = __uint_as_float(~(uint32_t)(key >> 32));
+        const double wd = floor((double)v * two36);
+        uint64_t w = 0;
+        if (base + e < N) {
+            if (wd >= 9007199254740992.0) flags |= PKV_DEV_RANGE; else w = (uint64_t)wd;
+            order[seg * (size_t)N + base + e] = (int32_t)(uint32_t)key;
+        }
+        local = sat_add(local, w);
+        skey[base + e] = local;  // thread-local inclusive sums, rebased below
+    }
+    // scan of the thread totals: within the wave by shuffles, across waves through LDS
+    const int lane = tid & (kWave - 1), wv = tid / kWave;
+    uint64_t incl = local;
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint64_t up = shfl_up_u64(incl, d);
+        if (lane >= d) incl = sat_add(incl, up);
+    }
+    if (lane == kWave - 1) wave_tot[wv] = incl;
+    __syncthreads();
+    uint64_t wave_base = 0, total = 0;
+    const int nw = nt / kWave;
+    for (int w = 0; w < nw; ++w) {
+        const uint64_t t = wave_tot[w];
+        if (w < wv) wave_base = sat_add(wave_base, t);
+        total = sat_add(total, t);
+    }
+    const uint64_t excl = sat_add(wave_base, incl - local);
+    if (total > (1ull << 53)) flags |= PKV_DEV_RANGE;
+    if (flags) atomicOr(&s_flags, flags);
+    const double dtotal = (double)total;
+    for (int e = 0; e < E; ++e) {
+        const int j = base + e;
+        if (j < N) {
+            const uint64_t c = sat_add(excl, skey[j]);
+            cum[seg * (size_t)N + j] = c;
+            if (prefix && total) prefix[seg * (size_t)N + j] = (float)((double)c / dtotal);
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        // invalid values win over a range overflow, which wins over an all-zero layer
+        int f = s_flags;
+        if (f & (PKV_DEV_NONFINITE | PKV_DEV_NEGATIVE)) f &= (PKV_DEV_NONFINITE | PKV_DEV_NEGATIVE);
+        else if (f & PKV_DEV_RANGE) f = PKV_DEV_RANGE;
+        else if (total == 0) f = PKV_DEV_ZERO_LAYER;
+        seg_status[seg] = f;
+    }
+}
+
+// One wavefront per sequence.  Lane l owns layer l (l < L <= 64); p1, p2, p live in every lane with
+// identical arithmetic, so control flow stays uniform and no iteration leaves the device.
+__global__ void __launch_bounds__(kWave)
+search_kernel(int L, int N, const uint64_t* __restrict__ cum, const int32_t* __restrict__ seg_status,
+              int64_t budget, int64_t tol, int max_iters, int fixup, int32_t* __restrict__ lengths,
+              double* __restrict__ p_out, int32_t* __restrict__ iters_out,
+              int64_t* __restrict__ raw_total_out, int32_t* __restrict__ status) {
+    __shared__ int s_sorted[kMaxL];
+    __shared__ int s_len[kMaxL];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const bool act = lane < L;
+    const uint64_t* c = cum + ((size_t)b * L + (act ? lane : 0)) * (size_t)N;  // c[k-1] = C_k
+
+    int st = act ? seg_status[(size_t)b * L + lane] : 0;
+    for (int d = 32; d > 0; d >>= 1) st |= __shfl_xor(st, d, kWave);
+    if (st) {
+        if (act) lengths[(size_t)b * L + lane] = 0;
+        if (lane == 0) { p_out[b] = 0.0; iters_out[b] = 0; raw_total_out[b] = 0; status[b] = st; }
+        return;
+    }
+    if (budget <= L || budget >= (int64_t)L * N) {
+        const bool all = budget > L;
+        if (act) lengths[(size_t)b * L + lane] = all ? N : 1;
+        if (lane == 0) {
+            p_out[b] = all ? 1.0 : 0.0; iters_out[b] = 0;
+            raw_total_out[b] = all ? (int64_t)L * N : L; status[b] = 0;
+        }
+        return;
+    }
+
+    const double T = act ? (double)c[N - 1] : 0.0;
+    // prefix lengths at the interval ends: k(p1 = 0) = 1, k(p2 = 1) = N.  The length is monotone in p,
+    // so the length at any midpoint lies between the lengths at the ends of the current interval.
+    int k_lo = 1, k_hi = N, k = 1;
+    double p1 = 0.0, p2 = 1.0, p = 0.5;
+    int iters = 0, K = 0;
+    for (int it = 1; it <= max_iters; ++it) {
+        const double mid = 0.5 * (p1 + p2);
+        if (mid == p1 || mid == p2) break;
+        p = mid;
+        const double thr = __dmul_rn(p, T);  // one rounded product, never contracted
+        int a = k_lo, e = k_hi;              // smallest k in [a, e] with C_k >= thr (k = e if none below)
+        while (a < e) {
+            const int m = (a + e) >> 1;
+            if ((double)c[m - 1] >= thr) e = m; else a = m + 1;
+        }
+        k = a;
+        int sum = act ? k : 0;
+        for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, kWave);
+        K = sum;
+        iters = it;
+        const int64_t delta = (int64_t)K - budget;
+        if ((delta < 0 ? -delta : delta) <= tol) break;
+        if (delta < 0) { p1 = p; k_lo = k; } else { p2 = p; k_hi = k; }
+    }
+    if (lane == 0) { p_out[b] = p; iters_out[b] = iters; raw_total_out[b] = K; status[b] = 0; }
+
+    if (!fixup || K == budget) {
+        if (act) lengths[(size_t)b * L + lane] = k;
+        return;
+    }
+    // proportional rescale, then largest remainders first (ties: lower layer)
+    const uint64_t num = act ? (uint64_t)k * (uint64_t)budget : 0;
+    int64_t bs = (int64_t)(num / (uint64_t)K);
+    bs = bs < 1 ? 1 : (bs > N ? N : bs);
+    const uint64_t rem = num % (uint64_t)K;
+    int sumb = act ? (int)bs : 0;
+    for (int d = 32; d > 0; d >>= 1) sumb += __shfl_xor(sumb, d, kWave);
+    int64_t dlt = budget - sumb;
+    const bool grow = dlt > 0;
+    int rank = 0;
+    for (int j = 0; j < L; ++j) {
+        const uint64_t rj = shfl_u64(rem, j);
+        const bool before = grow ? (rj > rem || (rj == rem && j < lane))
+                                 : (rj < rem || (rj == rem && j < lane));
+        rank += before ? 1 : 0;
+    }
+    if (act) { s_sorted[rank] = lane; s_len[lane] = (int)bs; }
+    __syncthreads();
+    if (lane == 0 && dlt != 0) {
+        // Walking the ranked layers cyclically, one token per visit: whole rounds are applied at once
+        // while no layer can hit its limit, the last partial round visits in rank order.
+        int64_t left = grow ? dlt : -dlt;
+        while (left > 0) {
+            int elig = 0;
+            int64_t room = N;
+            for (int i = 0; i < L; ++i) {
+                const int v = s_len[i];
+                const int r = grow ? N - v : v - 1;
+                if (r > 0) { ++elig; room = r < room ? r : room; }
+            }
+            if (elig == 0) break;  // cannot happen for L < budget < L*N
+            if (left >= elig) {
+                int64_t rounds = left / elig;
+                if (rounds > room) rounds = room;
+                for (int i = 0; i < L; ++i) {
+                    const int v = s_len[i];
+                    if ((grow ? N - v : v - 1) > 0) s_len[i] = v + (grow ? (int)rounds : -(int)rounds);
+                }
+                left -= rounds * elig;
+            } else {
+                for (int i = 0; i < L && left > 0; ++i) {
+                    const int l = s_sorted[i];
+                    const int v = s_len[l];
+                    if ((grow ? N - v : v - 1) > 0) { s_len[l] = v + (grow ? 1 : -1); --left; }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (act) lengths[(size_t)b * L + lane] = s_len[lane];
+}
+
+static int pow2_at_least(int n) { int p = 64; while (p < n) p <<= 1; return p; }
+
+size_t select_ws_bytes(int B, int L, int N) { (void)N; return (size_t)B * L * sizeof(int32_t); }
+
+hipError_t launch_select(int B, int L, int N, const float* importance, const pkv_select_params& pr,
+                         int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
+                         int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, hipStream_t st) {
+    int32_t* seg_status = (int32_t*)ws;
+    const int P = pow2_at_least(N);
+    int nt = P / 2;
+    if (nt < 64) nt = 64;
+    if (nt > 1024) nt = 1024;
+    const size_t lds = (size_t)P * sizeof(uint64_t);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)sort_prefix_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(sort_prefix_kernel, dim3(B * L), dim3(nt), lds, st, N, P, importance, order, cum,
+                       prefix, seg_status);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(search_kernel, dim3(B), dim3(kWave), 0, st, L, N, cum, seg_status,
+                       (int64_t)pr.budget_tokens, (int64_t)pr.tol_tokens, (int)pr.max_iters, (int)pr.fixup,
+                       lengths, p_out, iters, raw_total, status);
+    return hipGetLastError();
+}
+
+}  // namespace pkv

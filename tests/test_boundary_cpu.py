@@ -1,0 +1,117 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, and rejects bad arguments synchronously (no launch happens on these paths)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2412_03409_amd as P
+from paper_2412_03409_amd import binding as Bd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "prefixkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(prefixkv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = P.load()
+    names = declared_symbols()
+    assert {"prefixkv_importance", "prefixkv_select", "prefixkv_compact", "prefixkv_decode_attn"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert P.prefixkv_version() >= 100
+    assert P.prefixkv_status_string(0) == "ok"
+
+
+def test_workspace_queries():
+    dt = P.PKV_BF16
+    per = 1 * 32 * 32 * 680 * 4
+    per = (per + 255) // 256 * 256
+    assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 32, 32, 32, 680, 128, dt) == 2 * per
+    assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 32, 32, 32, 680, 128, dt, has_lse=True) == per
+    assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 32, 32, 32, 680, 128, dt) == 2 * 32 * 4
+    assert P.prefixkv_workspace_bytes(Bd.OP_DECODE, 1, 32, 32, 32, 680, 128, dt, cache_tokens=12544) > 0
+    # invalid shapes give 0
+    assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 65, 32, 32, 680, 128, dt) == 0
+    assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 32, 32, 32, 680, 96, dt) == 0
+    assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 32, 32, 5, 680, 128, dt) == 0
+    assert P.prefixkv_workspace_bytes(9, 2, 32, 32, 32, 680, 128, dt) == 0
+    assert P.prefixkv_cache_tokens_upper_bound(16, 4352, 32, 512) == 16 * (4352 + 32 * 512)
+
+
+def _shape(**kw):
+    d = dict(B=1, L=4, H=2, Hkv=2, N=128, D=64, dtype=P.PKV_F32)
+    d.update(kw)
+    return Bd._Shape(*[d[k] for k in ("B", "L", "H", "Hkv", "N", "D", "dtype")])
+
+
+FAKE = C.c_void_p(0x1000)  # never dereferenced: every call below fails validation first
+
+
+def test_importance_argument_errors():
+    lib = P.load()
+    st = Bd._Strides(4 * 2 * 128 * 64, 2 * 128 * 64, 128 * 64, 64)
+    call = lambda s, q=FAKE, k=FAKE, sc=FAKE, out=FAKE, qs=st, ws=FAKE, wsb=1 << 30: lib.prefixkv_importance(
+        C.byref(s), q, qs, k, st, sc, None, out, ws, wsb, None)
+    assert call(_shape(), q=None) == 1
+    assert call(_shape(), out=None) == 1
+    assert call(_shape(L=0)) == 2
+    assert call(_shape(L=65)) == 2
+    assert call(_shape(N=8193)) == 2
+    assert call(_shape(D=96)) == 2
+    assert call(_shape(H=3, Hkv=2)) == 2
+    assert call(_shape(dtype=7)) == 3
+    assert call(_shape(), qs=Bd._Strides(1, 1, 1, 63)) == 4
+    assert call(_shape(), q=C.c_void_p(0x1004)) == 4
+    assert call(_shape(), ws=None) == 5
+    assert call(_shape(), wsb=16) == 5
+
+
+def test_select_argument_errors():
+    lib = P.load()
+    def call(B=1, L=4, N=128, imp=FAKE, budget=10, tol=0, iters=64, lengths=FAKE, ws=FAKE, wsb=1 << 20):
+        prm = Bd._SelectParams(budget, tol, iters, 1)
+        return lib.prefixkv_select(B, L, N, imp, C.byref(prm), FAKE, FAKE, None, lengths, FAKE, FAKE, FAKE,
+                                   FAKE, ws, wsb, None)
+    assert call(imp=None) == 1
+    assert call(lengths=None) == 1
+    assert call(L=65) == 2
+    assert call(N=0) == 2
+    assert call(N=8193) == 2
+    assert call(budget=0) == 6
+    assert call(tol=-1) == 6
+    assert call(iters=0) == 6
+    assert call(ws=None) == 5
+    assert call(wsb=3) == 5
+
+
+def test_compact_and_decode_argument_errors():
+    lib = P.load()
+    st = Bd._Strides(4 * 2 * 128 * 64, 2 * 128 * 64, 128 * 64, 64)
+    s = _shape()
+    comp = lambda k=FAKE, cap=8, sh=s, ks=st: lib.prefixkv_compact(
+        C.byref(sh), k, ks, FAKE, st, FAKE, FAKE, cap, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None)
+    assert comp(k=None) == 1
+    assert comp(cap=-1) == 2
+    assert comp(sh=_shape(D=32)) == 2
+    assert comp(ks=Bd._Strides(0, 0, 0, 6)) == 4
+    dec = lambda l0=0, l1=4, q=FAKE, kn=FAKE, vn=FAKE, ws=FAKE, wsb=1 << 30, ct=1000: lib.prefixkv_decode_attn(
+        C.byref(s), l0, l1, q, kn, vn, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ct, ws, wsb, None)
+    assert dec(q=None) == 1
+    assert dec(kn=None) == 1          # k_new without v_new
+    assert dec(l0=2, l1=2) == 2
+    assert dec(l1=5) == 2
+    assert dec(ct=-1) == 2
+    assert dec(ws=None) == 5
+    assert dec(wsb=8) == 5
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        P.prefixkv_select(torch.ones(1, 2, 8), 4)

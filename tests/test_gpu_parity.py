@@ -1,0 +1,300 @@
+"""GPU parity: every stage of the HIP path, called through the C-ABI binding, against the CPU oracle
+on the same seeded inputs.  Bars: indices / lengths / integers bit-exact; importance within 1e-3
+relative; decode attention output within 2e-2 absolute."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2412_03409_amd as P
+from pkv_workloads import CONFIGS, make_decode, make_prefill, synthetic_importance
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+IMP_RTOL = 1e-3     # importance: relative, bf16 inputs, fp32 accumulation
+OUT_ATOL = 2e-2     # decode attention output: absolute
+
+
+def np32(t):
+    return t.detach().float().cpu().numpy()
+
+
+def rand_qk(seed, B, L, H, Hkv, N, D, dtype, smax=3.0, sinks=True):
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn((B, L, H, N, D), generator=g).to(dtype)
+    k = torch.randn((B, L, Hkv, N, D), generator=g)
+    if sinks:
+        k[:, :, :, 0] *= 4.0
+        k[:, :, :, N // 3] *= 4.0
+    k = k.to(dtype)
+    scale = ((torch.rand(L, generator=g) * (smax - 0.5) + 0.5) / D ** 0.5).float()
+    return q, k, scale
+
+
+def check_importance(got, want):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    err = np.abs(got - want) / np.maximum(np.abs(want), 1e-30)
+    bad = (err > IMP_RTOL) & (np.abs(got - want) > 1e-9)
+    assert not bad.any(), f"max rel err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+# --------------------------------------------------------------------------------------- importance
+@pytest.mark.parametrize("B,L,H,Hkv,N,D,dtype", [
+    (1, 4, 2, 2, 128, 64, torch.float32),      # the Tiny shape
+    (2, 2, 4, 2, 77, 128, torch.float32),      # fp32, GQA, ragged
+    (1, 2, 4, 4, 200, 128, torch.bfloat16),    # several 128-row tiles + ragged tail
+    (2, 3, 8, 2, 333, 64, torch.bfloat16),     # GQA, D = 64
+    (1, 1, 2, 2, 1, 128, torch.bfloat16),      # a single position
+    (1, 2, 2, 1, 31, 128, torch.bfloat16),     # less than one MFMA tile
+    (1, 1, 3, 3, 680, 128, torch.bfloat16),    # the LLaVA prompt length
+    (1, 1, 2, 2, 1100, 128, torch.bfloat16),   # beyond 1024
+])
+def test_importance_matches_oracle(B, L, H, Hkv, N, D, dtype):
+    q, k, scale = rand_qk(N + D + H, B, L, H, Hkv, N, D, dtype)
+    want, lse = oracle.importance(np32(q), np32(k), scale.numpy(), want_lse=True)
+    got = P.prefixkv_importance(q.to(DEV), k.to(DEV), scale.to(DEV))
+    check_importance(np32(got), want)
+    np.testing.assert_allclose(np32(got).sum(-1), N, rtol=1e-4)
+    # caller-supplied lse (from its own prefill attention) skips the first pass
+    got2 = P.prefixkv_importance(q.to(DEV), k.to(DEV), scale.to(DEV),
+                                 lse=torch.from_numpy(lse.astype(np.float32)).to(DEV))
+    check_importance(np32(got2), want)
+
+
+def test_importance_strided_inputs_and_determinism():
+    B, L, H, N, D = 1, 2, 4, 150, 128
+    q, k, scale = rand_qk(5, B, L, H, H, N, D, torch.bfloat16)
+    # a fused [B,L,H,N,2D] buffer holding q and k side by side: row stride 2D
+    qk = torch.cat([q, k], dim=-1).to(DEV)
+    qv, kv = qk[..., :D], qk[..., D:]
+    a = P.prefixkv_importance(qv, kv, scale.to(DEV))
+    b = P.prefixkv_importance(q.to(DEV), k.to(DEV), scale.to(DEV))
+    assert torch.equal(a, b)
+    check_importance(np32(a), oracle.importance(np32(q), np32(k), scale.numpy()))
+
+
+def test_importance_tiny_config_full():
+    w = CONFIGS["tiny"]
+    x = make_prefill(w)
+    want = oracle.importance(np32(x["q"]), np32(x["k"]), x["scale"].numpy())
+    got = P.prefixkv_importance(x["q"].to(DEV), x["k"].to(DEV), x["scale"].to(DEV))
+    check_importance(np32(got), want)
+
+
+# --------------------------------------------------------------------------------------- select
+def check_select(imp, budget, tol=0, max_iters=64, fixup=True):
+    want = oracle.select(imp.numpy(), budget, tol, max_iters, fixup)
+    got = P.prefixkv_select(imp.to(DEV), budget, tol, max_iters, fixup)
+    torch.cuda.synchronize()
+    st = got.status.cpu().numpy()
+    np.testing.assert_array_equal(st, want["status"])
+    np.testing.assert_array_equal(got.lengths.cpu().numpy(), want["lengths"])
+    np.testing.assert_array_equal(got.iters.cpu().numpy(), want["iters"])
+    np.testing.assert_array_equal(got.raw_total.cpu().numpy(), want["raw_total"])
+    np.testing.assert_array_equal(got.p.cpu().numpy(), want["p"])
+    ok = st == 0
+    np.testing.assert_array_equal(got.order.cpu().numpy()[ok], want["order"][ok])
+    np.testing.assert_array_equal(got.cum.cpu().numpy().view(np.uint64)[ok], want["cum"][ok])
+    np.testing.assert_array_equal(got.prefix.cpu().numpy()[ok], want["prefix"][ok])
+    return want
+
+
+@pytest.mark.parametrize("B,L,N", [(1, 1, 1), (1, 3, 5), (2, 4, 128), (3, 32, 680), (2, 40, 680),
+                                   (1, 64, 64), (2, 8, 8192), (1, 5, 1025), (2, 7, 2049)])
+@pytest.mark.parametrize("ties", [False, True])
+def test_select_bit_exact(B, L, N, ties):
+    imp = synthetic_importance(B, L, N, seed=B * 1000 + L * 10 + N, ties=ties)
+    total = L * N
+    for budget in sorted({1, L, L + 1, max(L + 1, total // 10), max(L + 1, total // 5), max(L + 1, total // 2),
+                          total - 1, total, total + 5}):
+        if budget >= 1:
+            check_select(imp, budget)
+    check_select(imp, max(L + 1, total // 5), tol=max(1, N // 20))
+    check_select(imp, max(L + 1, total // 5), max_iters=7)
+    check_select(imp, max(L + 1, total // 5), max_iters=9, fixup=False)
+    check_select(imp, max(L + 1, total // 2), tol=3, fixup=False)
+
+
+def test_select_identical_layers_need_the_rescale():
+    # all layers jump together, so most totals are unreachable: exercises stall + largest remainder
+    row = synthetic_importance(1, 1, 96, seed=3)[0, 0]
+    imp = row.repeat(2, 6, 1).contiguous()
+    for budget in (7, 100, 101, 333, 575):
+        want = check_select(imp, budget)
+        assert (want["lengths"].sum(-1) == budget).all()
+
+
+def test_select_status_words():
+    imp = synthetic_importance(6, 3, 50, seed=4)
+    imp[1, 2, 7] = float("nan")
+    imp[2, 0, 0] = float("inf")
+    imp[3, 1, 3] = -0.25
+    imp[4, 1, :] = 0.0
+    imp[5, 2, 9] = -0.0           # allowed
+    want = check_select(imp, 40)
+    assert want["status"].tolist() == [0, 1, 1, 2, 4, 0]
+    big = synthetic_importance(1, 2, 16, seed=5)
+    big[0, 1, :] = 2.0 ** 16
+    want = check_select(big, 9)
+    assert want["status"][0] == 8
+
+
+def test_select_on_device_importance_of_tiny_config():
+    w = CONFIGS["tiny"]
+    x = make_prefill(w)
+    imp = P.prefixkv_importance(x["q"].to(DEV), x["k"].to(DEV), x["scale"].to(DEV)).cpu()
+    want = check_select(imp, w.budget_tokens())   # both sides consume the SAME importance tensor
+    assert want["lengths"].sum() == w.budget_tokens()
+
+
+# --------------------------------------------------------------------------------------- compaction
+def run_compact(k, v, sel, cap, budget):
+    B, L = sel["lengths"].shape
+    tokens = P.prefixkv_cache_tokens_upper_bound(B, budget, L, cap)
+    got = P.prefixkv_compact(k.to(DEV), v.to(DEV), torch.from_numpy(sel["order"]).to(DEV),
+                             torch.from_numpy(sel["lengths"]).to(DEV), cap, tokens)
+    want = oracle.compact(np32(k), np32(v), sel["order"], sel["lengths"], cap)
+    return got, want
+
+
+def check_cache(got, want, dtype):
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(got.seg_off.cpu().numpy(), want["seg_off"])
+    np.testing.assert_array_equal(got.caps.cpu().numpy(), want["caps"])
+    np.testing.assert_array_equal(got.lens.cpu().numpy(), want["lens"])
+    B, L = want["lens"].shape
+    Hkv, D = want["Hkv"], want["D"]
+    kc, vc, kp = np32(got.kc), np32(got.vc), got.kept_pos.cpu().numpy()
+    for b in range(B):
+        for l in range(L):
+            n, off, cap = want["lens"][b, l], int(want["seg_off"][b, l]), int(want["caps"][b, l])
+            wkp = oracle.segment(want, "kept_pos", b, l)[:n]
+            nk = int((wkp >= 0).sum())          # slots appended during decode carry no prompt position
+            np.testing.assert_array_equal(kp[off:off + nk], wkp[:nk])
+            gk = kc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
+            gv = vc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
+            np.testing.assert_array_equal(gk, oracle.segment(want, "kc", b, l)[:, :n])
+            np.testing.assert_array_equal(gv, oracle.segment(want, "vc", b, l)[:, :n])
+
+
+@pytest.mark.parametrize("B,L,Hkv,N,D,dtype,frac", [
+    (1, 4, 2, 128, 64, torch.float32, 0.5),
+    (2, 3, 4, 333, 128, torch.bfloat16, 0.2),
+    (2, 2, 2, 70, 64, torch.bfloat16, 0.33),
+    (1, 2, 2, 100, 128, torch.float32, 1.0),
+    (1, 3, 1, 8192, 128, torch.bfloat16, 0.1),
+])
+def test_compact_bit_exact(B, L, Hkv, N, D, dtype, frac):
+    g = torch.Generator().manual_seed(N + D)
+    k = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+    v = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+    imp = synthetic_importance(B, L, N, seed=N)
+    budget = max(L + 1, int(frac * L * N))
+    sel = oracle.select(imp.numpy(), budget)
+    got, want = run_compact(k, v, sel, 5, budget)
+    check_cache(got, want, dtype)
+
+
+def test_compact_with_empty_segments():
+    B, L, Hkv, N, D = 2, 3, 2, 40, 64
+    g = torch.Generator().manual_seed(1)
+    k = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    v = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    imp = synthetic_importance(B, L, N, seed=9)
+    imp[1, 1, 3] = float("nan")            # sequence 1 is rejected: all its lengths are 0
+    sel = oracle.select(imp.numpy(), 30)
+    assert sel["lengths"][1].sum() == 0
+    got, want = run_compact(k, v, sel, 2, 30)
+    check_cache(got, want, torch.bfloat16)
+
+
+# --------------------------------------------------------------------------------------- decode
+def run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed, layer_range=None, zero_seq=False):
+    g = torch.Generator().manual_seed(seed)
+    k = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+    v = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+    scale = ((torch.rand(L, generator=g) * 2.5 + 0.5) / D ** 0.5).float()
+    imp = synthetic_importance(B, L, N, seed=seed)
+    if zero_seq:
+        imp[0, 0, 0] = float("nan")
+    budget = max(L + 1, int(frac * L * N))
+    sel = oracle.select(imp.numpy(), budget)
+    got, want = run_compact(k, v, sel, steps, budget)
+    state = P.DecodeState.create(got, B, L, H, N)
+    l0, l1 = layer_range or (0, L)
+    bf = dtype == torch.bfloat16
+    for t in range(steps + 1):
+        q = torch.randn((B, L, H, D), generator=g).to(dtype)
+        kn = torch.randn((B, L, Hkv, D), generator=g).to(dtype)
+        vn = torch.randn((B, L, Hkv, D), generator=g).to(dtype)
+        append = t < steps       # the last step attends without appending
+        o = P.prefixkv_decode_attn(got, q.to(DEV), kn.to(DEV) if append else None,
+                                   vn.to(DEV) if append else None, scale.to(DEV), N, l0, l1, state=state)
+        ref = oracle.decode_attn(want, np32(q), np32(kn) if append else None, np32(vn) if append else None,
+                                 scale.numpy(), l0, l1, out_bf16=bf)
+        torch.cuda.synchronize()
+        err = np.abs(np32(o)[:, l0:l1] - ref[:, l0:l1])
+        assert err.max() <= OUT_ATOL, f"step {t}: max abs err {err.max():.3e}"
+        np.testing.assert_array_equal(got.lens.cpu().numpy(), want["lens"])
+    check_cache(got, want, dtype)   # appended rows landed in the right slots, bit for bit
+
+
+@pytest.mark.parametrize("B,L,H,Hkv,N,D,dtype,frac,steps", [
+    (1, 4, 2, 2, 128, 64, torch.float32, 0.5, 8),       # the Tiny shape
+    (2, 3, 4, 4, 300, 128, torch.bfloat16, 0.3, 3),     # MHA, several chunks per segment
+    (2, 2, 8, 2, 500, 128, torch.bfloat16, 0.5, 2),     # GQA group of 4
+    (1, 2, 16, 2, 260, 64, torch.bfloat16, 0.6, 2),     # GQA group of 8, D = 64
+    (1, 2, 6, 2, 150, 128, torch.bfloat16, 0.4, 2),     # group of 3: falls back to 1 head per unit
+    (1, 2, 4, 2, 90, 128, torch.float32, 0.9, 2),       # fp32 rows of 512 B (two sub-blocks per chunk)
+    (1, 2, 2, 2, 63, 128, torch.bfloat16, 1.0, 2),      # 63 -> 64 -> 65 slots: crosses a chunk edge
+])
+def test_decode_matches_oracle(B, L, H, Hkv, N, D, dtype, frac, steps):
+    run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed=N + H)
+
+
+def test_decode_layer_range_and_rejected_sequence():
+    run_decode_case(2, 4, 4, 4, 100, 128, torch.bfloat16, 0.3, 2, seed=7, layer_range=(1, 3))
+    run_decode_case(2, 3, 4, 2, 100, 128, torch.bfloat16, 0.3, 2, seed=8, zero_seq=True)
+
+
+def test_full_budget_reproduces_full_cache_attention():
+    # budget of 100%: the compressed path must equal plain attention over the whole prefill cache
+    B, L, H, N, D = 1, 2, 4, 150, 128
+    g = torch.Generator().manual_seed(21)
+    k = torch.randn((B, L, H, N, D), generator=g).to(torch.bfloat16)
+    v = torch.randn((B, L, H, N, D), generator=g).to(torch.bfloat16)
+    q = torch.randn((B, L, H, D), generator=g).to(torch.bfloat16)
+    scale = torch.full((L,), 1.0 / D ** 0.5)
+    imp = synthetic_importance(B, L, N, seed=2).to(DEV)
+    sel = P.prefixkv_select(imp, L * N)
+    tokens = P.prefixkv_cache_tokens_upper_bound(B, L * N, L, 0)
+    cache = P.prefixkv_compact(k.to(DEV), v.to(DEV), sel.order, sel.lengths, 0, tokens)
+    o = P.prefixkv_decode_attn(cache, q.to(DEV), None, None, scale.to(DEV), N)
+    s = torch.einsum("blhd,blhnd->blhn", q.double(), k.double()) * scale.double()[None, :, None, None]
+    ref = torch.einsum("blhn,blhnd->blhd", torch.softmax(s, -1), v.double())
+    assert (o.cpu().double() - ref).abs().max() <= OUT_ATOL
+    assert torch.equal(cache.kc.view(k.shape).cpu(), k)
+
+
+# --------------------------------------------------------------------------------------- end to end
+def test_tiny_config_end_to_end():
+    w = CONFIGS["tiny"]
+    x, dec = make_prefill(w), make_decode(w)
+    imp = P.prefixkv_importance(x["q"].to(DEV), x["k"].to(DEV), x["scale"].to(DEV))
+    sel = P.prefixkv_select(imp, w.budget_tokens())
+    tokens = P.prefixkv_cache_tokens_upper_bound(w.B, w.budget_tokens(), w.L, w.decode_steps)
+    cache = P.prefixkv_compact(x["k"].to(DEV), x["v"].to(DEV), sel.order, sel.lengths, w.decode_steps, tokens)
+    o_sel = oracle.select(imp.cpu().numpy(), w.budget_tokens())      # same importance tensor on both sides
+    np.testing.assert_array_equal(sel.lengths.cpu().numpy(), o_sel["lengths"])
+    np.testing.assert_array_equal(sel.order.cpu().numpy(), o_sel["order"])
+    assert int(sel.lengths.sum()) == w.budget_tokens()
+    o_cache = oracle.compact(np32(x["k"]), np32(x["v"]), o_sel["order"], o_sel["lengths"], w.decode_steps)
+    state = P.DecodeState.create(cache, w.B, w.L, w.H, w.N)
+    for t in range(w.decode_steps):
+        o = P.prefixkv_decode_attn(cache, dec["q"][t].to(DEV), dec["k"][t].to(DEV), dec["v"][t].to(DEV),
+                                   x["scale"].to(DEV), w.N, state=state)
+        ref = oracle.decode_attn(o_cache, np32(dec["q"][t]), np32(dec["k"][t]), np32(dec["v"][t]),
+                                 x["scale"].numpy())
+        assert np.abs(np32(o) - ref).max() <= OUT_ATOL
+    check_cache(cache, o_cache, torch.float32)
