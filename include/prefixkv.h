@@ -63,11 +63,11 @@ typedef void *pkv_stream; /* hipStream_t */
 int prefixkv_version(void);
 const char *prefixkv_status_string(int status);
 
-/* Workspace bytes for op = PKV_OP_*.  `cache_tokens` is only used by PKV_OP_DECODE (the number of
- * token slots allocated in kc/vc); pass 0 otherwise.  `has_lse` (PKV_OP_IMPORTANCE) = the caller
- * will pass its own lse.  Returns 0 for invalid arguments. */
+/* Workspace bytes for op = PKV_OP_*.  `has_lse` (PKV_OP_IMPORTANCE only) = the caller will pass
+ * its own lse.  Returns 0 for invalid arguments and for stages that need no scratch (compaction
+ * and decode attention: their ws may be NULL). */
 enum { PKV_OP_IMPORTANCE = 0, PKV_OP_SELECT = 1, PKV_OP_COMPACT = 2, PKV_OP_DECODE = 3 };
-size_t prefixkv_workspace_bytes(int op, const pkv_shape *shape, int64_t cache_tokens, int has_lse);
+size_t prefixkv_workspace_bytes(int op, const pkv_shape *shape, int has_lse);
 
 /* ---- Stage 1: KV importance (Sec. 3.2, the causal score matrix a_l^{i,m,n} and the importance
  * metric I_l^n = Average_i(sum_m a_l^{i,m,n})).
@@ -139,19 +139,21 @@ int prefixkv_compact(const pkv_shape *shape, const void *k, pkv_strides ks, cons
 int64_t prefixkv_cache_tokens_upper_bound(int B, int64_t budget_tokens, int L, int decode_capacity);
 
 /* ---- Stage 4b: one decode step over layers [l0,l1) (Sec. 3.1: the newest token's query
- * interacts with the cached KV vectors).
+ * interacts with the cached KV vectors).  One kernel launch.
  * If k_new/v_new are non-NULL, the new token's key/value of every (b,l,kv head) are first stored
  * in slot lens[b,l] of the segment and lens[b,l] becomes lens[b,l]+1 (the caller guarantees
  * lens < caps; a full segment drops the append and the step attends over the old slots).  Then
  *   out[b,l,h,:] = sum_j softmax_j(scale[l] * q[b,l,h,:].kc_j) * vc_j   over the lens slots of kv
  * head g(h); an empty segment gives zeros.  fp32 softmax and accumulation; out in shape->dtype.
  *   q, out [dev] [B,L,H,D] dense;  k_new, v_new [dev] [B,L,Hkv,D] dense or NULL (both)
- *   kc, vc, seg_off, caps as produced by prefixkv_compact;  lens [dev] in/out
- *   cache_tokens = token slots allocated in kc/vc (>= sum of caps); sizes the workspace. */
+ *   kc, vc, seg_off, caps as produced by prefixkv_compact
+ *   lens [dev] in/out: plain lengths below 2^20 before and after the call.  WHILE the launch runs
+ *       the library keeps a completion count in the bits above 2^20 of each entry, so lens must
+ *       not be read or written by anything else until the launch has finished.  H <= 2048. */
 int prefixkv_decode_attn(const pkv_shape *shape, int l0, int l1, const void *q, const void *k_new,
                          const void *v_new, const float *scale, void *kc, void *vc,
                          const int64_t *seg_off, const int32_t *caps, int32_t *lens, void *out,
-                         int64_t cache_tokens, void *ws, size_t ws_bytes, pkv_stream stream);
+                         void *ws, size_t ws_bytes, pkv_stream stream);
 
 #ifdef __cplusplus
 }

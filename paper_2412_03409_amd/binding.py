@@ -6,6 +6,7 @@ workspace are allocated here with torch (the library itself never allocates) unl
 from __future__ import annotations
 
 import ctypes as C
+import os
 from dataclasses import dataclass
 from pathlib import Path
 from typing import Optional
@@ -45,21 +46,24 @@ def lib_path() -> Path:
     return _LIB_PATH
 
 
-def load() -> C.CDLL:
-    """Load libprefixkv.so; raises if it has not been built (no fallback exists)."""
+def load(path: Optional[str] = None) -> C.CDLL:
+    """Load libprefixkv.so (or another build of it at `path`); raises if it has not been built
+    (no fallback exists)."""
     global _lib
-    if _lib is not None:
+    if _lib is not None and path is None:
         return _lib
-    if not _LIB_PATH.exists():
-        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2412_03409_amd.build` "
+    path = path or os.environ.get("PKV_LIB_PATH")   # an alternative build of the same library
+    lib_file = Path(path) if path else _LIB_PATH
+    if not lib_file.exists():
+        raise ImportError(f"{lib_file} is missing: build it with `python -m paper_2412_03409_amd.build` "
                           "(hipcc, gfx950); there is no CPU path")
-    L = C.CDLL(str(_LIB_PATH))
+    L = C.CDLL(str(lib_file))
     vp, i32, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
     L.prefixkv_version.restype = C.c_int
     L.prefixkv_status_string.restype = C.c_char_p
     L.prefixkv_status_string.argtypes = [C.c_int]
     L.prefixkv_workspace_bytes.restype = sz
-    L.prefixkv_workspace_bytes.argtypes = [i32, C.POINTER(_Shape), i64, i32]
+    L.prefixkv_workspace_bytes.argtypes = [i32, C.POINTER(_Shape), i32]
     L.prefixkv_importance.restype = C.c_int
     L.prefixkv_importance.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, vp, vp, sz, vp]
     L.prefixkv_select.restype = C.c_int
@@ -72,7 +76,7 @@ def load() -> C.CDLL:
     L.prefixkv_cache_tokens_upper_bound.argtypes = [i32, i64, i32, i32]
     L.prefixkv_decode_attn.restype = C.c_int
     L.prefixkv_decode_attn.argtypes = [C.POINTER(_Shape), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
-                                       i64, vp, sz, vp]
+                                       vp, sz, vp]
     _lib = L
     return L
 
@@ -125,10 +129,9 @@ def _ws(nbytes: int, device, ws: Optional[torch.Tensor]) -> torch.Tensor:
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
-def prefixkv_workspace_bytes(op: int, B, L, H, Hkv, N, D, dtype, cache_tokens: int = 0,
-                             has_lse: bool = False) -> int:
+def prefixkv_workspace_bytes(op: int, B, L, H, Hkv, N, D, dtype, has_lse: bool = False) -> int:
     s = _shape(B, L, H, Hkv, N, D, dtype)
-    return int(load().prefixkv_workspace_bytes(op, C.byref(s), cache_tokens, int(has_lse)))
+    return int(load().prefixkv_workspace_bytes(op, C.byref(s), int(has_lse)))
 
 
 def prefixkv_cache_tokens_upper_bound(B: int, budget_tokens: int, L: int, decode_capacity: int) -> int:
@@ -152,7 +155,7 @@ def prefixkv_importance(q: torch.Tensor, k: torch.Tensor, scale: torch.Tensor,
     s = _shape(B, L, H, Hkv, N, D, _dtype_code(q))
     if out is None:
         out = torch.empty((B, L, N), dtype=torch.float32, device=q.device)
-    nbytes = load().prefixkv_workspace_bytes(OP_IMPORTANCE, C.byref(s), 0, int(lse is not None))
+    nbytes = load().prefixkv_workspace_bytes(OP_IMPORTANCE, C.byref(s), int(lse is not None))
     w = _ws(nbytes, q.device, ws)
     rc = load().prefixkv_importance(C.byref(s), _ptr(q), _strides5(q), _ptr(k), _strides5(k), _ptr(scale),
                                     _ptr(lse), _ptr(out), _ptr(w), w.numel() * w.element_size(), _stream())
@@ -249,22 +252,10 @@ def prefixkv_compact(k: torch.Tensor, v: torch.Tensor, order: torch.Tensor, leng
     return out
 
 
-@dataclass
-class DecodeState:
-    """Pre-sized workspace for prefixkv_decode_attn (reused across steps)."""
-    ws: torch.Tensor
-
-    @staticmethod
-    def create(cache: CompactResult, B: int, L: int, H: int, N: int) -> "DecodeState":
-        dt = PKV_F32 if cache.kc.dtype == torch.float32 else PKV_BF16
-        nbytes = prefixkv_workspace_bytes(OP_DECODE, B, L, H, cache.Hkv, N, cache.D, dt, cache.cache_tokens)
-        return DecodeState(torch.empty(max(nbytes, 256), dtype=torch.uint8, device=cache.kc.device))
-
-
 def prefixkv_decode_attn(cache: CompactResult, q: torch.Tensor, k_new: Optional[torch.Tensor],
                          v_new: Optional[torch.Tensor], scale: torch.Tensor, N: int,
-                         l0: int = 0, l1: Optional[int] = None, out: Optional[torch.Tensor] = None,
-                         state: Optional[DecodeState] = None) -> torch.Tensor:
+                         l0: int = 0, l1: Optional[int] = None,
+                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """One decode step over layers [l0,l1): q [B,L,H,D], k_new/v_new [B,L,Hkv,D] or None
     -> out [B,L,H,D].  Appends in place and advances cache.lens on the device."""
     _need_cuda(q, k_new, v_new, scale, out)
@@ -279,14 +270,10 @@ def prefixkv_decode_attn(cache: CompactResult, q: torch.Tensor, k_new: Optional[
         raise ValueError("scale must be contiguous f32 [L]")
     if out is None:
         out = torch.empty((B, L, H, D), dtype=q.dtype, device=q.device)
-    if state is None:
-        state = DecodeState.create(cache, B, L, H, N)
     s = _shape(B, L, H, cache.Hkv, N, D, _dtype_code(q))
-    w = state.ws
     rc = load().prefixkv_decode_attn(C.byref(s), int(l0), int(l1), _ptr(q), _ptr(k_new), _ptr(v_new),
                                      _ptr(scale), _ptr(cache.kc), _ptr(cache.vc), _ptr(cache.seg_off),
-                                     _ptr(cache.caps), _ptr(cache.lens), _ptr(out), int(cache.cache_tokens),
-                                     _ptr(w), w.numel() * w.element_size(), _stream())
+                                     _ptr(cache.caps), _ptr(cache.lens), _ptr(out), None, 0, _stream())
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_decode_attn")
     return out

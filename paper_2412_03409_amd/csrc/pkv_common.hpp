@@ -52,10 +52,10 @@ hipError_t launch_compact(const pkv_shape& s, const void* k, Strides ks, const v
                           int64_t* seg_off, int32_t* caps, void* kc, void* vc, int32_t* kept_pos,
                           int32_t* lens, void* ws, hipStream_t st);
 
-size_t decode_ws_bytes(const pkv_shape& s, int64_t cache_tokens);
+size_t decode_ws_bytes(const pkv_shape& s);
 hipError_t launch_decode(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
                          const void* v_new, const float* scale, void* kc, void* vc,
                          const int64_t* seg_off, const int32_t* caps, int32_t* lens, void* out,
-                         int64_t cache_tokens, void* ws, hipStream_t st);
+                         hipStream_t st);
 
 }  // namespace pkv

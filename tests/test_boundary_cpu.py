@@ -35,7 +35,7 @@ def test_workspace_queries():
     assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 32, 32, 32, 680, 128, dt) == 2 * per
     assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 32, 32, 32, 680, 128, dt, has_lse=True) == per
     assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 32, 32, 32, 680, 128, dt) == 2 * 32 * 4
-    assert P.prefixkv_workspace_bytes(Bd.OP_DECODE, 1, 32, 32, 32, 680, 128, dt, cache_tokens=12544) > 0
+    assert P.prefixkv_workspace_bytes(Bd.OP_DECODE, 1, 32, 32, 32, 680, 128, dt) == 0
     # invalid shapes give 0
     assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 65, 32, 32, 680, 128, dt) == 0
     assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 32, 32, 32, 680, 96, dt) == 0
@@ -100,15 +100,14 @@ def test_compact_and_decode_argument_errors():
     assert comp(cap=-1) == 2
     assert comp(sh=_shape(D=32)) == 2
     assert comp(ks=Bd._Strides(0, 0, 0, 6)) == 4
-    dec = lambda l0=0, l1=4, q=FAKE, kn=FAKE, vn=FAKE, ws=FAKE, wsb=1 << 30, ct=1000: lib.prefixkv_decode_attn(
-        C.byref(s), l0, l1, q, kn, vn, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, ct, ws, wsb, None)
+    dec = lambda l0=0, l1=4, q=FAKE, kn=FAKE, vn=FAKE, sh=s: lib.prefixkv_decode_attn(
+        C.byref(sh), l0, l1, q, kn, vn, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None)
     assert dec(q=None) == 1
     assert dec(kn=None) == 1          # k_new without v_new
     assert dec(l0=2, l1=2) == 2
     assert dec(l1=5) == 2
-    assert dec(ct=-1) == 2
-    assert dec(ws=None) == 5
-    assert dec(wsb=8) == 5
+    assert dec(sh=_shape(H=4096, Hkv=2)) == 2
+    assert dec(q=C.c_void_p(0x1008)) == 4
 
 
 def test_binding_refuses_cpu_tensors():

@@ -221,7 +221,6 @@ def run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed, layer_range=No
     budget = max(L + 1, int(frac * L * N))
     sel = oracle.select(imp.numpy(), budget)
     got, want = run_compact(k, v, sel, steps, budget)
-    state = P.DecodeState.create(got, B, L, H, N)
     l0, l1 = layer_range or (0, L)
     bf = dtype == torch.bfloat16
     for t in range(steps + 1):
@@ -230,7 +229,7 @@ def run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed, layer_range=No
         vn = torch.randn((B, L, Hkv, D), generator=g).to(dtype)
         append = t < steps       # the last step attends without appending
         o = P.prefixkv_decode_attn(got, q.to(DEV), kn.to(DEV) if append else None,
-                                   vn.to(DEV) if append else None, scale.to(DEV), N, l0, l1, state=state)
+                                   vn.to(DEV) if append else None, scale.to(DEV), N, l0, l1)
         ref = oracle.decode_attn(want, np32(q), np32(kn) if append else None, np32(vn) if append else None,
                                  scale.numpy(), l0, l1, out_bf16=bf)
         torch.cuda.synchronize()
@@ -248,6 +247,9 @@ def run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed, layer_range=No
     (1, 2, 6, 2, 150, 128, torch.bfloat16, 0.4, 2),     # group of 3: falls back to 1 head per unit
     (1, 2, 4, 2, 90, 128, torch.float32, 0.9, 2),       # fp32 rows of 512 B (two sub-blocks per chunk)
     (1, 2, 2, 2, 63, 128, torch.bfloat16, 1.0, 2),      # 63 -> 64 -> 65 slots: crosses a chunk edge
+    (1, 2, 4, 4, 1500, 128, torch.bfloat16, 0.7, 2),    # N > 1024: 4-wavefront launch shape
+    (1, 2, 8, 2, 4200, 128, torch.bfloat16, 0.8, 2),    # N > 4096: 8-wavefront launch shape, GQA
+    (1, 1, 2, 2, 5000, 64, torch.float32, 0.9, 1),      # long fp32 segment
 ])
 def test_decode_matches_oracle(B, L, H, Hkv, N, D, dtype, frac, steps):
     run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed=N + H)
@@ -290,11 +292,35 @@ def test_tiny_config_end_to_end():
     np.testing.assert_array_equal(sel.order.cpu().numpy(), o_sel["order"])
     assert int(sel.lengths.sum()) == w.budget_tokens()
     o_cache = oracle.compact(np32(x["k"]), np32(x["v"]), o_sel["order"], o_sel["lengths"], w.decode_steps)
-    state = P.DecodeState.create(cache, w.B, w.L, w.H, w.N)
     for t in range(w.decode_steps):
         o = P.prefixkv_decode_attn(cache, dec["q"][t].to(DEV), dec["k"][t].to(DEV), dec["v"][t].to(DEV),
-                                   x["scale"].to(DEV), w.N, state=state)
+                                   x["scale"].to(DEV), w.N)
         ref = oracle.decode_attn(o_cache, np32(dec["q"][t]), np32(dec["k"][t]), np32(dec["v"][t]),
                                  x["scale"].numpy())
         assert np.abs(np32(o) - ref).max() <= OUT_ATOL
     check_cache(cache, o_cache, torch.float32)
+
+
+def test_decode_loop_graph_replays_match_eager():
+    # the decode loop captured as one HIP graph: several replays, with eager work and synchronisations
+    # between them, must each reproduce the eager outputs and the final cache bit for bit
+    from paper_2412_03409_amd.pipeline import HotPath
+    w = CONFIGS["tiny"].with_(decode_steps=6)
+    x, dec = make_prefill(w), make_decode(w)
+    hp = HotPath(x["q"].to(DEV), x["k"].to(DEV), x["v"].to(DEV), x["scale"].to(DEV), w.budget_tokens(), w.decode_steps)
+    dq, dk, dv = dec["q"].to(DEV), dec["k"].to(DEV), dec["v"].to(DEV)
+    hp.run_importance(); hp.run_select(); hp.run_compact()
+    hp.run_decode_loop(dq, dk, dv)
+    torch.cuda.synchronize()
+    want_out, want_kc, want_lens = hp.out.clone(), hp.cache.kc.clone(), hp.cache.lens.clone()
+    hp.capture_decode_loop(dq, dk, dv)
+    for rep in range(4):
+        hp.out.zero_()
+        hp.run_importance(); hp.run_select(); hp.run_compact()      # eager work between replays
+        torch.cuda.synchronize()
+        hp.replay_decode_loop()
+        torch.cuda.synchronize()
+        assert torch.equal(hp.out, want_out), f"replay {rep}"
+        assert torch.equal(hp.cache.lens, want_lens), f"replay {rep}"
+        # compare occupied slots only (the rest of the buffer is never written)
+        assert torch.equal(torch.nan_to_num(hp.cache.kc), torch.nan_to_num(want_kc)), f"replay {rep}"
