@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--decode-steps", type=int, default=None)
     ap.add_argument("--no-graph", action="store_true", help="launch every decode step from Python")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
+                    help="only run the plain copy kernel on BYTES (for calibrating rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures ONE GPU (the path shards over the batch with no exchange); "
@@ -57,6 +59,15 @@ def main() -> int:
     from pkv_workloads import CONFIGS, make_decode, make_prefill
 
     P.load()
+    if args.calibrate_copy:
+        n = args.calibrate_copy // 16 * 16
+        src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+        for _ in range(5):
+            P.prefixkv_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration_copy_bytes": n, "launches": 5}))
+        return 0
     w = CONFIGS[args.config]
     if args.decode_steps is not None:
         w = w.with_(decode_steps=args.decode_steps)

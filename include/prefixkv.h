@@ -155,6 +155,12 @@ int prefixkv_decode_attn(const pkv_shape *shape, int l0, int l1, const void *q, 
                          const int64_t *seg_off, const int32_t *caps, int32_t *lens, void *out,
                          void *ws, size_t ws_bytes, pkv_stream stream);
 
+/* Measurement aid, not part of the method: a plain device-to-device copy kernel of a known size
+ * (bytes % 16 == 0, 16-byte aligned pointers).  It reads `bytes` and writes `bytes`, which is what
+ * hardware byte counters are calibrated against when a kernel's HBM traffic is reported. */
+int prefixkv_calibration_copy(void *dst /* [dev] */, const void *src /* [dev] */, size_t bytes,
+                              pkv_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

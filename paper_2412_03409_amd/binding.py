@@ -77,6 +77,8 @@ def load(path: Optional[str] = None) -> C.CDLL:
     L.prefixkv_decode_attn.restype = C.c_int
     L.prefixkv_decode_attn.argtypes = [C.POINTER(_Shape), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                        vp, sz, vp]
+    L.prefixkv_calibration_copy.restype = C.c_int
+    L.prefixkv_calibration_copy.argtypes = [vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -277,3 +279,14 @@ def prefixkv_decode_attn(cache: CompactResult, q: torch.Tensor, k_new: Optional[
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_decode_attn")
     return out
+
+
+def prefixkv_calibration_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain copy kernel of src's size into dst (byte-counter calibration aid)."""
+    _need_cuda(dst, src)
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("dst too small")
+    rc = load().prefixkv_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_calibration_copy")

@@ -6,6 +6,13 @@ using namespace pkv;
 
 namespace {
 
+// Plain copy, 16 bytes per lane, grid-stride: the known-size reference for calibrating byte counters.
+__global__ void __launch_bounds__(256) calibration_copy_kernel(const uint4* __restrict__ src,
+                                                               uint4* __restrict__ dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 bool shape_ok(const pkv_shape* s) {
     return s->B >= 1 && s->L >= 1 && s->L <= kMaxL && s->H >= 1 && s->Hkv >= 1 && s->H % s->Hkv == 0 &&
            s->N >= 1 && s->N <= kMaxN && (s->D == 64 || s->D == 128);
@@ -120,6 +127,15 @@ int prefixkv_decode_attn(const pkv_shape* s, int l0, int l1, const void* q, cons
     const hipError_t e = launch_decode(*s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, lens, out,
                                        (hipStream_t)stream);
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int prefixkv_calibration_copy(void* dst, const void* src, size_t bytes, pkv_stream stream) {
+    if (!dst || !src) return PKV_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return PKV_ERR_DIM;
+    if (!aligned16(dst) || !aligned16(src)) return PKV_ERR_STRIDE;
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(8192), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4*)src, (uint4*)dst, bytes / 16);
+    return hipGetLastError() == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
 
 }  // extern "C"
