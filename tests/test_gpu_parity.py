@@ -34,6 +34,7 @@ def rand_qk(seed, B, L, H, Hkv, N, D, dtype, smax=3.0, sinks=True):
 
 def check_importance(got, want):
     got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    assert np.isfinite(got).all(), "non-finite importance"
     err = np.abs(got - want) / np.maximum(np.abs(want), 1e-30)
     bad = (err > IMP_RTOL) & (np.abs(got - want) > 1e-9)
     assert not bad.any(), f"max rel err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
