@@ -58,15 +58,16 @@ def _f32(a):
     return np.ascontiguousarray(a, dtype=np.float32)
 
 
-def importance(q, k, scale, want_lse: bool = False):
-    """q [B,L,H,N,D], k [B,L,Hkv,N,D], scale [L] -> importance [B,L,N] f32 (and lse [B,L,H,N] f64)."""
+def importance(q, k, scale, want_lse: bool = False, m_lo: int = 0):
+    """q [B,L,H,N,D], k [B,L,Hkv,N,D], scale [L] -> importance [B,L,N] f32 (and lse [B,L,H,N] f64).
+    m_lo > 0: only query rows m >= m_lo are processed; columns n >= m_lo are complete, the rest NaN."""
     q, k, scale = _f32(q), _f32(k), _f32(scale)
     B, L, H, N, D = q.shape
     Hkv = k.shape[2]
     assert k.shape == (B, L, Hkv, N, D) and H % Hkv == 0 and scale.shape == (L,)
     imp = np.empty((B, L, N), dtype=np.float32)
     lse = np.empty((B, L, H, N), dtype=np.float64) if want_lse else None
-    lib().pkvo_importance(B, L, H, Hkv, N, D, _p(q), _p(k), _p(scale), _p(imp), _p(lse))
+    lib().pkvo_importance(B, L, H, Hkv, N, D, _p(q), _p(k), _p(scale), _p(imp), _p(lse), int(m_lo))
     return (imp, lse) if want_lse else imp
 
 

@@ -39,9 +39,12 @@ int pkvo_threads(void) {
  * Query head h reads KV head h / (H/Hkv).  The paper's literal formula has scale = 1.
  * q [B,L,H,N,D], k [B,L,Hkv,N,D], scale [L] -> importance [B,L,N] (fp32 cast at the very end).
  * If lse_out != NULL it receives log(sum_j exp(scale*q_m.k_j)) per row, [B,L,H,N] fp64.
+ * m_lo restricts the work to query rows m >= m_lo: since position n only receives attention from rows
+ * m >= n, importance[.., n] is complete for every n >= m_lo (and NaN below), which lets a test check the
+ * tail columns of a long prompt without paying for all rows.  m_lo = 0 computes everything.
  * ------------------------------------------------------------------------------------------- */
 void pkvo_importance(int B, int L, int H, int Hkv, int N, int D, const float *q, const float *k,
-                     const float *scale, float *importance, double *lse_out) {
+                     const float *scale, float *importance, double *lse_out, int m_lo) {
     const int grp = H / Hkv;
     const long units = (long)B * L * H;
     double *colsum = (double *)calloc((size_t)units * N, sizeof(double));
@@ -57,7 +60,7 @@ void pkvo_importance(int B, int L, int H, int Hkv, int N, int D, const float *q,
             const float *kh = k + (((size_t)b * L + l) * Hkv + h / grp) * (size_t)N * D;
             double *cs = colsum + (size_t)u * N;
             const double sc = (double)scale[l];
-            for (int m = 0; m < N; ++m) {
+            for (int m = m_lo; m < N; ++m) {
                 double mx = -INFINITY;
                 for (int n = 0; n <= m; ++n) {
                     double dot = 0.0;
@@ -82,7 +85,7 @@ void pkvo_importance(int B, int L, int H, int Hkv, int N, int D, const float *q,
         for (int n = 0; n < N; ++n) {
             double acc = 0.0;
             for (int h = 0; h < H; ++h) acc += colsum[((size_t)bl * H + h) * N + n];
-            importance[(size_t)bl * N + n] = (float)(acc / (double)H);
+            importance[(size_t)bl * N + n] = n >= m_lo ? (float)(acc / (double)H) : NAN;
         }
     free(colsum);
 }

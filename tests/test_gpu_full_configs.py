@@ -1,0 +1,136 @@
+"""GPU parity at the full sizes of the five workload configurations, through the same pre-allocated
+pipeline and launch configuration the benchmark times (HIP graph for the decode loop).
+
+The whole batch runs on the GPU; the oracle checks everything for the small configs and a sampled
+sequence (for the long-context config also sampled layers and the tail columns of the importance)
+for the large ones, plus properties that hold at any size.  Inputs are generated on the device from
+seeded generators; the sampled slices are copied back for the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2412_03409_amd as P
+from paper_2412_03409_amd.pipeline import HotPath
+from pkv_workloads import CONFIGS, make_decode, make_prefill
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+IMP_RTOL, OUT_ATOL = 1e-3, 2e-2
+
+
+def f32(t):
+    return t.detach().float().cpu().numpy()
+
+
+def check_importance(got, want):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    assert np.isfinite(got).all()
+    err = np.abs(got - want)
+    bad = (err > IMP_RTOL * np.abs(want)) & (err > 1e-9)
+    assert not bad.any(), f"max rel err {(err / np.maximum(np.abs(want), 1e-30)).max():.3e}"
+
+
+def run_config(name, budget, sample_b, steps, imp_layers=None, imp_tail=None):
+    w = CONFIGS[name]
+    Bk = w.budget_tokens(budget)
+    x = make_prefill(w, device=DEV)
+    dec = make_decode(w, steps=steps, device=DEV)
+    hp = HotPath(x["q"], x["k"], x["v"], x["scale"], Bk, steps)
+    hp.run_importance(); hp.run_select(); hp.run_compact()
+    torch.cuda.synchronize()
+    scale = x["scale"].cpu().numpy()
+    imp = hp.importance.cpu().numpy()
+
+    # ---- properties that hold at any size, over the whole batch
+    np.testing.assert_allclose(imp.sum(-1), w.N, rtol=2e-4)        # every causal softmax row sums to one
+    assert (imp[..., 0] >= 1 - 1e-3).all() and (imp[..., -1] <= 1 + 1e-3).all() and (imp >= 0).all()
+    assert (hp.sel.status.cpu().numpy() == 0).all()
+    lengths = hp.sel.lengths.cpu().numpy()
+    assert (lengths.sum(1) == Bk).all() and lengths.min() >= 1 and lengths.max() <= w.N
+    order = hp.sel.order.cpu().numpy()
+    assert (np.sort(order, axis=-1) == np.arange(w.N)).all()       # every row is a permutation
+    cum = hp.sel.cum.cpu().numpy().view(np.uint64)
+    assert (np.diff(cum.astype(np.int64), axis=-1) >= 0).all()
+
+    # ---- importance against the oracle on the sampled sequence
+    b = sample_b
+    layers = list(range(w.L)) if imp_layers is None else imp_layers
+    m_lo = 0 if imp_tail is None else w.N - imp_tail
+    for l0 in ([None] if imp_layers is None else layers):
+        sl = slice(None) if l0 is None else slice(l0, l0 + 1)
+        want = oracle.importance(f32(x["q"][b:b + 1, sl]), f32(x["k"][b:b + 1, sl]), scale[sl], m_lo=m_lo)
+        check_importance(imp[b:b + 1, sl, m_lo:], want[..., m_lo:])
+
+    # ---- selection: both sides consume the GPU's importance tensor; everything is bit-exact
+    want = oracle.select(imp, Bk)
+    np.testing.assert_array_equal(order, want["order"])
+    np.testing.assert_array_equal(cum, want["cum"])
+    np.testing.assert_array_equal(hp.sel.prefix.cpu().numpy(), want["prefix"])
+    np.testing.assert_array_equal(lengths, want["lengths"])
+    np.testing.assert_array_equal(hp.sel.p.cpu().numpy(), want["p"])
+    np.testing.assert_array_equal(hp.sel.iters.cpu().numpy(), want["iters"])
+    np.testing.assert_array_equal(hp.sel.raw_total.cpu().numpy(), want["raw_total"])
+
+    # ---- ragged layout over the whole batch, then compaction + decode of the sampled sequence
+    caps = hp.cache.caps.cpu().numpy()
+    seg_off = hp.cache.seg_off.cpu().numpy()
+    np.testing.assert_array_equal(caps, lengths + steps)
+    np.testing.assert_array_equal(seg_off.ravel(), np.concatenate([[0], np.cumsum(caps.ravel())[:-1]]))
+    np.testing.assert_array_equal(hp.cache.lens.cpu().numpy(), lengths)
+    ocache = oracle.compact(f32(x["k"][b:b + 1]), f32(x["v"][b:b + 1]), want["order"][b:b + 1],
+                            want["lengths"][b:b + 1], steps)
+
+    def compare_cache():
+        Hkv, D = w.Hkv, w.D
+        lo, hi = int(seg_off[b, 0]), int(seg_off[b, -1] + caps[b, -1])
+        kc = f32(hp.cache.kc[lo * Hkv * D:hi * Hkv * D])
+        vc = f32(hp.cache.vc[lo * Hkv * D:hi * Hkv * D])
+        kp = hp.cache.kept_pos[lo:hi].cpu().numpy()
+        for l in range(w.L):
+            n, cap, off = int(ocache["lens"][0, l]), int(caps[b, l]), int(seg_off[b, l]) - lo
+            gk = kc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
+            gv = vc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
+            np.testing.assert_array_equal(gk, oracle.segment(ocache, "kc", 0, l)[:, :n])
+            np.testing.assert_array_equal(gv, oracle.segment(ocache, "vc", 0, l)[:, :n])
+            nk = int(lengths[b, l])
+            np.testing.assert_array_equal(kp[off:off + nk], oracle.segment(ocache, "kept_pos", 0, l)[:nk])
+
+    compare_cache()
+    # the decode loop exactly as the benchmark runs it: one HIP graph of `steps` launches
+    dq, dk, dv = dec["q"], dec["k"], dec["v"]
+    hp.capture_decode_loop(dq, dk, dv)
+    hp.run_compact()
+    hp.replay_decode_loop()
+    torch.cuda.synchronize()
+    bf = w.dtype == "bf16"
+    for t in range(steps):
+        ref = oracle.decode_attn(ocache, f32(dq[t, b:b + 1]), f32(dk[t, b:b + 1]), f32(dv[t, b:b + 1]), scale,
+                                 out_bf16=bf)
+        err = np.abs(f32(hp.out[t, b:b + 1]) - ref).max()
+        assert err <= OUT_ATOL, f"decode step {t}: max abs err {err:.3e}"
+    np.testing.assert_array_equal(hp.cache.lens.cpu().numpy(), lengths + steps)
+    compare_cache()       # appended rows landed in the right slots, bit for bit
+    assert torch.isfinite(hp.out.float()).all()
+
+
+def test_tiny_full():
+    run_config("tiny", 0.5, 0, steps=8)
+
+
+def test_llava7b_b1_full():
+    run_config("llava7b_b1", 0.2, 0, steps=4)
+
+
+@pytest.mark.parametrize("budget", [0.1, 0.2, 0.5])
+def test_llava7b_b16_sampled_sequence(budget):
+    run_config("llava7b_b16", budget, sample_b=11, steps=2)
+
+
+def test_llava13b_b8_sampled_sequence():
+    run_config("llava13b_b8", 0.2, sample_b=5, steps=2)
+
+
+@pytest.mark.timeout(400)
+def test_gqa_long_sampled_sequence_and_tail_columns():
+    run_config("gqa_long", 0.1, sample_b=2, steps=2, imp_layers=[0, 19], imp_tail=160)

@@ -449,3 +449,11 @@ def test_empty_cache_segment_gives_zero_output():
     q = np.ones((B, L, 2, 8), np.float32)
     out = oracle.decode_attn(cache, q, None, None, np.ones(L, np.float32))
     assert (out == 0).all()
+
+
+def test_importance_row_restriction_keeps_tail_columns_exact():
+    q, k, sc = rng_qk(31, 1, 2, 3, 3, 40, 8)
+    full = oracle.importance(q, k, sc)
+    tail = oracle.importance(q, k, sc, m_lo=25)
+    np.testing.assert_array_equal(tail[..., 25:], full[..., 25:])
+    assert np.isnan(tail[..., :25]).all()
