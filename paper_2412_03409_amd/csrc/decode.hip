@@ -39,6 +39,14 @@ struct DecodeParams {
     unsigned char* out;           // [B,L,H,D]
 };
 
+// Cache rows are read once per decode step and never reused by the same launch: stream them past the
+// caches (nontemporal) so that they do not evict each other on the way in.
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+__device__ __forceinline__ uint4 load_stream16(const unsigned char* p) {
+    const u32x4_t t = __builtin_nontemporal_load((const u32x4_t*)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+
 template <bool BF16>
 __device__ __forceinline__ void unpack16(const uint4& r, float* f) {
     if constexpr (BF16) {
@@ -73,15 +81,15 @@ __device__ __forceinline__ void attend_block(const unsigned char* __restrict__ k
     for (int i = 0; i < NI; ++i) {
         const uint32_t o_i = lane_off + (uint32_t)(i * RPI) * (uint32_t)row_bytes;
         if constexpr (!TAIL) {
-            kr[i] = *(const uint4*)(kseg + o_i);
-            vr[i] = *(const uint4*)(vseg + o_i);
+            kr[i] = load_stream16(kseg + o_i);
+            vr[i] = load_stream16(vseg + o_i);
         } else {
             const int r = r0 + i * RPI + rg;
             kr[i] = make_uint4(0, 0, 0, 0); vr[i] = make_uint4(0, 0, 0, 0);
             if (r < len) {
                 const bool isnew = app && r == len_old;
-                kr[i] = *(const uint4*)(isnew ? knew + sub * 16 : kseg + o_i);
-                vr[i] = *(const uint4*)(isnew ? vnew + sub * 16 : vseg + o_i);
+                kr[i] = load_stream16(isnew ? knew + sub * 16 : kseg + o_i);
+                vr[i] = load_stream16(isnew ? vnew + sub * 16 : vseg + o_i);
                 if (isnew && writer) {
                     *(uint4*)(kw + o_i) = kr[i];
                     *(uint4*)(vw + o_i) = vr[i];
