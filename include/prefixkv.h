@@ -118,6 +118,32 @@ int prefixkv_select(int B, int L, int N, const float *importance /* [dev] [B,L,N
                     int64_t *raw_total, int32_t *status, void *ws, size_t ws_bytes,
                     pkv_stream stream);
 
+/* ---- Stage 2 alone, for offline estimation (Sec. 3.3, last paragraph: the retention ratios R_l
+ * are estimated once from a few random samples and reused).  Same order / cum / prefix as
+ * prefixkv_select and the same status bits, no search.  status [B] i32 = OR over the sequence's
+ * layers; a sequence with a non-zero status has unspecified order/cum/prefix.  The workspace size
+ * is that of PKV_OP_SELECT.  prefix may be NULL. */
+int prefixkv_rank(int B, int L, int N, const float *importance /* [dev] [B,L,N] */, int32_t *order,
+                  uint64_t *cum, float *prefix, int32_t *status, void *ws, size_t ws_bytes,
+                  pkv_stream stream);
+
+/* ---- Offline configuration (Sec. 3.3, last paragraph; Sec. 4.3 "offline estimation").
+ * sample_lengths [dev] i32 [S,L]: the per-layer lengths prefixkv_select found for S calibration
+ * sequences (each of them lengths/N = the sample's retention ratios R_l, same N for all samples).
+ * The shared configuration is the mean of the samples' ratios, brought to the exact budget: with
+ * weight_l = sum_s sample_lengths[s,l] and K = sum_l weight_l,
+ *   lengths_l = weight_l*budget_tokens/K rounded down and clamped to [1,N], then the remaining
+ *   tokens one per layer by largest remainder (ties: lower layer), cyclically, exactly as the
+ *   rescale of prefixkv_select.  budget_tokens <= L -> all 1; >= L*N -> all N; K == 0 (every
+ *   sample was rejected by its status word) -> all 0.
+ * The paper fixes only "estimate offline from random samples"; the mean over samples is this
+ * library's reading.  lengths_out [dev] i32 [B_out,L]: the same row B_out times, ready to be the
+ * `lengths` of prefixkv_compact together with each sequence's own `order` from prefixkv_rank.
+ * 1 <= S <= 65536, B_out >= 1.  No workspace. */
+int prefixkv_offline_config(int S, int L, int N, const int32_t *sample_lengths,
+                            int64_t budget_tokens, int B_out, int32_t *lengths_out,
+                            pkv_stream stream);
+
 /* ---- Stage 4a: compaction (Sec. 3.2: the top R_l proportion of KV vectors is retained in each
  * head of layer l; Fig. 3(a): layer-wise compressed cache).
  * The kept set of (b,l) is order[b,l,0..lengths[b,l]); it is stored in ascending position.

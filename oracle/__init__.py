@@ -112,6 +112,29 @@ def select(imp, budget_tokens: int, tol_tokens: int = 0, max_iters: int = 64, fi
     return out
 
 
+def rank(imp):
+    """Stage 2 only: importance [B,L,N] -> dict(order, cum, prefix, status[B]) (no search)."""
+    imp = _f32(imp)
+    B, L, N = imp.shape
+    out = dict(order=np.zeros((B, L, N), np.int32), cum=np.zeros((B, L, N), np.uint64),
+               prefix=np.zeros((B, L, N), np.float32), status=np.zeros(B, np.int32))
+    for b in range(B):
+        for l in range(L):
+            st, o, c, pf = sort_prefix_layer(imp[b, l])
+            out["status"][b] |= st
+            out["order"][b, l], out["cum"][b, l], out["prefix"][b, l] = o, c, pf
+    return out
+
+
+def offline_config(sample_lengths, N: int, budget_tokens: int):
+    """sample_lengths [S,L] i32 from S calibration sequences -> shared lengths [L] i32."""
+    sl = np.ascontiguousarray(sample_lengths, dtype=np.int32)
+    S, L = sl.shape
+    out = np.zeros(L, dtype=np.int32)
+    lib().pkvo_offline_config(S, L, int(N), _p(sl), C.c_int64(budget_tokens), _p(out))
+    return out
+
+
 def compact(k, v, order, lengths, decode_capacity: int):
     """k,v [B,L,Hkv,N,D]; order [B,L,N]; lengths [B,L] -> ragged cache dict.
     kc/vc are flat f32 arrays of sum(caps)*Hkv*D elements (segment (b,l) = [Hkv][cap][D] at token

@@ -169,6 +169,37 @@ static int pkvo_rem_asc(const void *a, const void *b) {
     return (x->l > y->l) - (x->l < y->l);
 }
 
+/* Proportional rescale of per-layer weights to an exact token budget (the "scale the resulting global
+ * prefix configuration to meet the target budget" step of Sec. 3.3): lengths[l] = weight[l]*budget/K
+ * rounded down and clamped to [1,N] (K = sum of the weights), then the missing tokens go one per
+ * layer in order of largest remainder (ties: lower layer), cyclically; a surplus is taken back in order
+ * of smallest remainder.  Requires L < budget < L*N and K > 0. */
+static void pkvo_rescale(int L, int N, const int64_t *weight, int64_t K, int64_t budget, int32_t *lengths) {
+    pkvo_rem *r = (pkvo_rem *)malloc(sizeof(pkvo_rem) * (size_t)L);
+    int64_t sum = 0;
+    for (int l = 0; l < L; ++l) {
+        const uint64_t num = (uint64_t)weight[l] * (uint64_t)budget;
+        int64_t base = (int64_t)(num / (uint64_t)K);
+        if (base < 1) base = 1;
+        if (base > N) base = N;
+        r[l].rem = num % (uint64_t)K;
+        r[l].l = l;
+        lengths[l] = (int32_t)base;
+        sum += base;
+    }
+    int64_t dlt = budget - sum;
+    if (dlt > 0) {
+        qsort(r, (size_t)L, sizeof(pkvo_rem), pkvo_rem_desc);
+        for (int i = 0; dlt > 0; i = (i + 1) % L)
+            if (lengths[r[i].l] < N) { lengths[r[i].l] += 1; --dlt; }
+    } else if (dlt < 0) {
+        qsort(r, (size_t)L, sizeof(pkvo_rem), pkvo_rem_asc);
+        for (int i = 0; dlt < 0; i = (i + 1) % L)
+            if (lengths[r[i].l] > 1) { lengths[r[i].l] -= 1; ++dlt; }
+    }
+    free(r);
+}
+
 /* ---------------------------------------------------------------------------------------------
  * Stage 3 -- Algorithm 1 (binary search for the retention ratio p) for ONE sequence, followed by
  * the "scale the configuration to meet the budget" step of Sec. 3.3's last paragraph.
@@ -208,30 +239,30 @@ void pkvo_search(int L, int N, const uint64_t *cum, int64_t budget, int64_t tol,
     *p_out = p; *iters_out = iters; *raw_total_out = K;
     if (!fixup || K == budget) return;
 
-    /* Proportional rescale of the configuration to the budget, largest remainder first. */
-    pkvo_rem *r = (pkvo_rem *)malloc(sizeof(pkvo_rem) * (size_t)L);
-    int64_t sum = 0;
-    for (int l = 0; l < L; ++l) {
-        const uint64_t num = (uint64_t)lengths[l] * (uint64_t)budget;
-        int64_t base = (int64_t)(num / (uint64_t)K);
-        if (base < 1) base = 1;
-        if (base > N) base = N;
-        r[l].rem = num % (uint64_t)K;
-        r[l].l = l;
-        lengths[l] = (int32_t)base;
-        sum += base;
-    }
-    int64_t dlt = budget - sum;
-    if (dlt > 0) {
-        qsort(r, (size_t)L, sizeof(pkvo_rem), pkvo_rem_desc);
-        for (int i = 0; dlt > 0; i = (i + 1) % L)
-            if (lengths[r[i].l] < N) { lengths[r[i].l] += 1; --dlt; }
-    } else if (dlt < 0) {
-        qsort(r, (size_t)L, sizeof(pkvo_rem), pkvo_rem_asc);
-        for (int i = 0; dlt < 0; i = (i + 1) % L)
-            if (lengths[r[i].l] > 1) { lengths[r[i].l] -= 1; ++dlt; }
-    }
-    free(r);
+    int64_t *wgt = (int64_t *)malloc(sizeof(int64_t) * (size_t)L);
+    for (int l = 0; l < L; ++l) wgt[l] = lengths[l];
+    pkvo_rescale(L, N, wgt, K, budget, lengths);
+    free(wgt);
+}
+
+/* Offline estimation of the global prefix configuration (Sec. 3.3, last paragraph: the configuration is
+ * derived from a few random samples and then adopted for every input, which avoids the online search).
+ * The paper does not give the aggregation rule; this reading averages the per-sample ratios R_l, i.e.
+ * weights layer l by the sum of its lengths over the S samples, and rescales those weights to the
+ * budget of the deployed prompt length N with the same largest-remainder rule.
+ * sample_lengths [S,L] (all samples share one prompt length) -> lengths [L].
+ * budget <= L gives all 1, budget >= L*N all N; an all-zero sample set gives all 0. */
+void pkvo_offline_config(int S, int L, int N, const int32_t *sample_lengths, int64_t budget,
+                         int32_t *lengths) {
+    int64_t *wgt = (int64_t *)calloc((size_t)L, sizeof(int64_t));
+    int64_t K = 0;
+    for (int s = 0; s < S; ++s)
+        for (int l = 0; l < L; ++l) { wgt[l] += sample_lengths[(size_t)s * L + l]; K += sample_lengths[(size_t)s * L + l]; }
+    if (K == 0) { for (int l = 0; l < L; ++l) lengths[l] = 0; }
+    else if (budget <= L) { for (int l = 0; l < L; ++l) lengths[l] = 1; }
+    else if (budget >= (int64_t)L * N) { for (int l = 0; l < L; ++l) lengths[l] = N; }
+    else pkvo_rescale(L, N, wgt, K, budget, lengths);
+    free(wgt);
 }
 
 /* Stages 2+3 for a batch: importance [B,L,N] -> order, cum, prefix (may be NULL), lengths [B,L],

@@ -69,6 +69,10 @@ def load(path: Optional[str] = None) -> C.CDLL:
     L.prefixkv_select.restype = C.c_int
     L.prefixkv_select.argtypes = [i32, i32, i32, vp, C.POINTER(_SelectParams), vp, vp, vp, vp, vp, vp, vp,
                                   vp, vp, sz, vp]
+    L.prefixkv_rank.restype = C.c_int
+    L.prefixkv_rank.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.prefixkv_offline_config.restype = C.c_int
+    L.prefixkv_offline_config.argtypes = [i32, i32, i32, vp, i64, i32, vp, vp]
     L.prefixkv_compact.restype = C.c_int
     L.prefixkv_compact.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, i32, vp, vp, vp,
                                    vp, vp, vp, vp, sz, vp]
@@ -205,6 +209,54 @@ def prefixkv_select(importance: torch.Tensor, budget_tokens: int, tol_tokens: in
                                 w.numel() * w.element_size(), _stream())
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_select")
+    return out
+
+
+@dataclass
+class RankResult:
+    order: torch.Tensor      # [B,L,N] i32
+    cum: torch.Tensor        # [B,L,N] i64 holding the u64 bit pattern
+    prefix: Optional[torch.Tensor]  # [B,L,N] f32
+    status: torch.Tensor     # [B] i32
+
+
+def prefixkv_rank(importance: torch.Tensor, want_prefix: bool = True, out: Optional[RankResult] = None,
+                  ws: Optional[torch.Tensor] = None) -> RankResult:
+    """importance [B,L,N] f32 -> per-layer ranking and cumulative priority, without the search."""
+    _need_cuda(importance, ws)
+    if importance.dtype != torch.float32 or importance.dim() != 3 or not importance.is_contiguous():
+        raise ValueError("importance must be contiguous f32 [B,L,N]")
+    B, L, N = importance.shape
+    dev = importance.device
+    if out is None:
+        out = RankResult(
+            order=torch.empty((B, L, N), dtype=torch.int32, device=dev),
+            cum=torch.empty((B, L, N), dtype=torch.int64, device=dev),
+            prefix=torch.empty((B, L, N), dtype=torch.float32, device=dev) if want_prefix else None,
+            status=torch.empty(B, dtype=torch.int32, device=dev))
+    w = _ws(B * L * 4, dev, ws)
+    rc = load().prefixkv_rank(B, L, N, _ptr(importance), _ptr(out.order), _ptr(out.cum), _ptr(out.prefix),
+                              _ptr(out.status), _ptr(w), w.numel() * w.element_size(), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_rank")
+    return out
+
+
+def prefixkv_offline_config(sample_lengths: torch.Tensor, N: int, budget_tokens: int, B_out: int = 1,
+                            out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """sample_lengths [S,L] i32 (device) -> shared per-layer lengths, repeated: [B_out,L] i32."""
+    _need_cuda(sample_lengths, out)
+    if sample_lengths.dtype != torch.int32 or sample_lengths.dim() != 2 or not sample_lengths.is_contiguous():
+        raise ValueError("sample_lengths must be contiguous i32 [S,L]")
+    S, L = sample_lengths.shape
+    if out is None:
+        out = torch.empty((B_out, L), dtype=torch.int32, device=sample_lengths.device)
+    elif out.dtype != torch.int32 or out.shape != (B_out, L) or not out.is_contiguous():
+        raise ValueError("out must be contiguous i32 [B_out,L]")
+    rc = load().prefixkv_offline_config(S, L, int(N), _ptr(sample_lengths), int(budget_tokens), int(B_out),
+                                        _ptr(out), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_offline_config")
     return out
 
 

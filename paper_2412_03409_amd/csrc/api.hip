@@ -87,6 +87,25 @@ int prefixkv_select(int B, int L, int N, const float* importance, const pkv_sele
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
 
+int prefixkv_rank(int B, int L, int N, const float* importance, int32_t* order, uint64_t* cum, float* prefix,
+                  int32_t* status, void* ws, size_t ws_bytes, pkv_stream stream) {
+    if (!importance || !order || !cum || !status) return PKV_ERR_NULL;
+    if (B < 1 || L < 1 || L > kMaxL || N < 1 || N > kMaxN) return PKV_ERR_DIM;
+    if (!ws || ws_bytes < select_ws_bytes(B, L, N)) return PKV_ERR_WORKSPACE;
+    const hipError_t e = launch_rank(B, L, N, importance, order, cum, prefix, status, ws, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int prefixkv_offline_config(int S, int L, int N, const int32_t* sample_lengths, int64_t budget_tokens,
+                            int B_out, int32_t* lengths_out, pkv_stream stream) {
+    if (!sample_lengths || !lengths_out) return PKV_ERR_NULL;
+    if (S < 1 || S > 65536 || L < 1 || L > kMaxL || N < 1 || N > kMaxN || B_out < 1) return PKV_ERR_DIM;
+    if (budget_tokens < 1) return PKV_ERR_BUDGET;
+    const hipError_t e = launch_offline_config(S, L, N, sample_lengths, budget_tokens, B_out, lengths_out,
+                                               (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
 int prefixkv_compact(const pkv_shape* s, const void* k, pkv_strides ks, const void* v, pkv_strides vs,
                      const int32_t* order, const int32_t* lengths, int decode_capacity, int64_t* seg_off,
                      int32_t* caps, void* kc, void* vc, int32_t* kept_pos, int32_t* lens, void* ws,

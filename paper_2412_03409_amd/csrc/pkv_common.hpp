@@ -46,6 +46,11 @@ hipError_t launch_select(int B, int L, int N, const float* importance, const pkv
                          int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
                          int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, hipStream_t st);
 
+hipError_t launch_rank(int B, int L, int N, const float* importance, int32_t* order, uint64_t* cum,
+                       float* prefix, int32_t* status, void* ws, hipStream_t st);
+hipError_t launch_offline_config(int S, int L, int N, const int32_t* sample_lengths, int64_t budget,
+                                 int copies, int32_t* lengths, hipStream_t st);
+
 size_t compact_ws_bytes(const pkv_shape& s);
 hipError_t launch_compact(const pkv_shape& s, const void* k, Strides ks, const void* v, Strides vs,
                           const int32_t* order, const int32_t* lengths, int decode_capacity,

@@ -128,6 +128,68 @@ __global__ void sort_prefix_kernel(int N, int P, const float* __restrict__ impor
     }
 }
 
+// Proportional rescale of per-layer weights to an exact token budget, by one wavefront (lane l = layer l):
+// out[l] = weight_l * budget / K rounded down and clamped to [1, N]; the missing tokens go one per layer in
+// order of largest remainder (ties: lower layer), cyclically; a surplus is taken back by smallest remainder.
+// Whole rounds of the cyclic walk are applied at once while no layer can hit its limit, the last partial
+// round visits in rank order: equal to the one-token-at-a-time walk.  Requires L < budget < L*N, K > 0.
+// `out` may be global or shared memory; s_sorted / s_len are kMaxL ints of shared scratch.
+__device__ __forceinline__ void rescale_wave(int L, int N, uint64_t weight, uint64_t K, int64_t budget,
+                                             int32_t* out, int* s_sorted, int* s_len) {
+    const int lane = threadIdx.x;
+    const bool act = lane < L;
+    const uint64_t num = act ? weight * (uint64_t)budget : 0;
+    int64_t bs = (int64_t)(num / K);
+    bs = bs < 1 ? 1 : (bs > N ? N : bs);
+    const uint64_t rem = num % K;
+    int sumb = act ? (int)bs : 0;
+    for (int d = 32; d > 0; d >>= 1) sumb += __shfl_xor(sumb, d, kWave);
+    int64_t dlt = budget - sumb;
+    const bool grow = dlt > 0;
+    int rank = 0;
+    for (int j = 0; j < L; ++j) {
+        const uint64_t rj = shfl_u64(rem, j);
+        const bool before = grow ? (rj > rem || (rj == rem && j < lane))
+                                 : (rj < rem || (rj == rem && j < lane));
+        rank += before ? 1 : 0;
+    }
+    __syncthreads();
+    if (act) { s_sorted[rank] = lane; s_len[lane] = (int)bs; }
+    __syncthreads();
+    if (lane == 0 && dlt != 0) {
+        int64_t left = grow ? dlt : -dlt;
+        while (left > 0) {
+            int elig = 0;
+            int64_t room = N;
+            for (int i = 0; i < L; ++i) {
+                const int v = s_len[i];
+                const int r = grow ? N - v : v - 1;
+                if (r > 0) { ++elig; room = r < room ? r : room; }
+            }
+            if (elig == 0) break;  // cannot happen for L < budget < L*N
+            if (left >= elig) {
+                int64_t rounds = left / elig;
+                if (rounds > room) rounds = room;
+                for (int i = 0; i < L; ++i) {
+                    const int v = s_len[i];
+                    if ((grow ? N - v : v - 1) > 0) s_len[i] = v + (grow ? (int)rounds : -(int)rounds);
+                }
+                left -= rounds * elig;
+            } else {
+                for (int i = 0; i < L && left > 0; ++i) {
+                    const int l = s_sorted[i];
+                    const int v = s_len[l];
+                    if ((grow ? N - v : v - 1) > 0) { s_len[l] = v + (grow ? 1 : -1); --left; }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const int res = act ? s_len[lane] : 0;
+    __syncthreads();
+    if (act) out[lane] = res;
+}
+
 // One wavefront per sequence.  Lane l owns layer l (l < L <= 64); p1, p2, p live in every lane with
 // identical arithmetic, so control flow stays uniform and no iteration leaves the device.
 __global__ void __launch_bounds__(kWave)
@@ -189,56 +251,46 @@ search_kernel(int L, int N, const uint64_t* __restrict__ cum, const int32_t* __r
         if (act) lengths[(size_t)b * L + lane] = k;
         return;
     }
-    // proportional rescale, then largest remainders first (ties: lower layer)
-    const uint64_t num = act ? (uint64_t)k * (uint64_t)budget : 0;
-    int64_t bs = (int64_t)(num / (uint64_t)K);
-    bs = bs < 1 ? 1 : (bs > N ? N : bs);
-    const uint64_t rem = num % (uint64_t)K;
-    int sumb = act ? (int)bs : 0;
-    for (int d = 32; d > 0; d >>= 1) sumb += __shfl_xor(sumb, d, kWave);
-    int64_t dlt = budget - sumb;
-    const bool grow = dlt > 0;
-    int rank = 0;
-    for (int j = 0; j < L; ++j) {
-        const uint64_t rj = shfl_u64(rem, j);
-        const bool before = grow ? (rj > rem || (rj == rem && j < lane))
-                                 : (rj < rem || (rj == rem && j < lane));
-        rank += before ? 1 : 0;
+    rescale_wave(L, N, act ? (uint64_t)k : 0, (uint64_t)K, budget, lengths + (size_t)b * L, s_sorted, s_len);
+}
+
+// Offline configuration (Sec. 3.3, last paragraph): the lengths of S calibration sequences are summed per
+// layer (averaging the per-sample ratios R_l) and rescaled to the budget of the deployed prompt length N.
+// One wavefront; the same row is written `copies` times so that it can be used as a [B,L] lengths array.
+__global__ void __launch_bounds__(kWave)
+offline_config_kernel(int S, int L, int N, const int32_t* __restrict__ sample_lengths, int64_t budget,
+                      int copies, int32_t* __restrict__ lengths) {
+    __shared__ int s_sorted[kMaxL];
+    __shared__ int s_len[kMaxL];
+    const int lane = threadIdx.x;
+    const bool act = lane < L;
+    long long w = 0;
+    if (act)
+        for (int s = 0; s < S; ++s) w += sample_lengths[(size_t)s * L + lane];
+    long long K = w;
+    for (int d = 32; d > 0; d >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)K, d, kWave);
+        const uint32_t hi = __shfl_xor((uint32_t)((unsigned long long)K >> 32), d, kWave);
+        K += (long long)(((unsigned long long)hi << 32) | lo);
     }
-    if (act) { s_sorted[rank] = lane; s_len[lane] = (int)bs; }
-    __syncthreads();
-    if (lane == 0 && dlt != 0) {
-        // Walking the ranked layers cyclically, one token per visit: whole rounds are applied at once
-        // while no layer can hit its limit, the last partial round visits in rank order.
-        int64_t left = grow ? dlt : -dlt;
-        while (left > 0) {
-            int elig = 0;
-            int64_t room = N;
-            for (int i = 0; i < L; ++i) {
-                const int v = s_len[i];
-                const int r = grow ? N - v : v - 1;
-                if (r > 0) { ++elig; room = r < room ? r : room; }
-            }
-            if (elig == 0) break;  // cannot happen for L < budget < L*N
-            if (left >= elig) {
-                int64_t rounds = left / elig;
-                if (rounds > room) rounds = room;
-                for (int i = 0; i < L; ++i) {
-                    const int v = s_len[i];
-                    if ((grow ? N - v : v - 1) > 0) s_len[i] = v + (grow ? (int)rounds : -(int)rounds);
-                }
-                left -= rounds * elig;
-            } else {
-                for (int i = 0; i < L && left > 0; ++i) {
-                    const int l = s_sorted[i];
-                    const int v = s_len[l];
-                    if ((grow ? N - v : v - 1) > 0) { s_len[l] = v + (grow ? 1 : -1); --left; }
-                }
-            }
-        }
+    const bool trivial = K == 0 || budget <= L || budget >= (int64_t)L * N;
+    if (trivial) {
+        if (act) s_len[lane] = K == 0 ? 0 : (budget <= L ? 1 : N);
+    } else {
+        rescale_wave(L, N, (uint64_t)w, (uint64_t)K, budget, s_len, s_sorted, s_len);
     }
     __syncthreads();
-    if (act) lengths[(size_t)b * L + lane] = s_len[lane];
+    if (act)
+        for (int c = 0; c < copies; ++c) lengths[(size_t)c * L + lane] = s_len[lane];
+}
+
+// Per-sequence status word = OR of its layers' status words (used when stage 2 runs without the search).
+__global__ void __launch_bounds__(kWave)
+status_reduce_kernel(int L, const int32_t* __restrict__ seg_status, int32_t* __restrict__ status) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    int st = lane < L ? seg_status[(size_t)b * L + lane] : 0;
+    for (int d = 32; d > 0; d >>= 1) st |= __shfl_xor(st, d, kWave);
+    if (lane == 0) status[b] = st;
 }
 
 static int pow2_at_least(int n) { int p = 64; while (p < n) p <<= 1; return p; }
@@ -266,6 +318,34 @@ hipError_t launch_select(int B, int L, int N, const float* importance, const pkv
     hipLaunchKernelGGL(search_kernel, dim3(B), dim3(kWave), 0, st, L, N, cum, seg_status,
                        (int64_t)pr.budget_tokens, (int64_t)pr.tol_tokens, (int)pr.max_iters, (int)pr.fixup,
                        lengths, p_out, iters, raw_total, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_rank(int B, int L, int N, const float* importance, int32_t* order, uint64_t* cum,
+                       float* prefix, int32_t* status, void* ws, hipStream_t st) {
+    int32_t* seg_status = (int32_t*)ws;
+    const int P = pow2_at_least(N);
+    int nt = P / 2;
+    if (nt < 64) nt = 64;
+    if (nt > 1024) nt = 1024;
+    const size_t lds = (size_t)P * sizeof(uint64_t);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void*)sort_prefix_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(sort_prefix_kernel, dim3(B * L), dim3(nt), lds, st, N, P, importance, order, cum,
+                       prefix, seg_status);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(status_reduce_kernel, dim3(B), dim3(kWave), 0, st, L, seg_status, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_offline_config(int S, int L, int N, const int32_t* sample_lengths, int64_t budget,
+                                 int copies, int32_t* lengths, hipStream_t st) {
+    hipLaunchKernelGGL(offline_config_kernel, dim3(1), dim3(kWave), 0, st, S, L, N, sample_lengths, budget,
+                       copies, lengths);
     return hipGetLastError();
 }
 

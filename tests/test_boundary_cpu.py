@@ -90,6 +90,27 @@ def test_select_argument_errors():
     assert call(wsb=3) == 5
 
 
+def test_rank_and_offline_config_argument_errors():
+    lib = P.load()
+    rank = lambda B=1, L=4, N=128, imp=FAKE, st=FAKE, ws=FAKE, wsb=1 << 20: lib.prefixkv_rank(
+        B, L, N, imp, FAKE, FAKE, None, st, ws, wsb, None)
+    assert rank(imp=None) == 1
+    assert rank(st=None) == 1
+    assert rank(L=0) == 2
+    assert rank(N=8193) == 2
+    assert rank(ws=None) == 5
+    assert rank(wsb=15) == 5
+    off = lambda S=3, L=4, N=128, sl=FAKE, budget=100, Bo=2, out=FAKE: lib.prefixkv_offline_config(
+        S, L, N, sl, budget, Bo, out, None)
+    assert off(sl=None) == 1
+    assert off(out=None) == 1
+    assert off(S=0) == 2
+    assert off(S=65537) == 2
+    assert off(L=65) == 2
+    assert off(Bo=0) == 2
+    assert off(budget=0) == 6
+
+
 def test_compact_and_decode_argument_errors():
     lib = P.load()
     st = Bd._Strides(4 * 2 * 128 * 64, 2 * 128 * 64, 128 * 64, 64)

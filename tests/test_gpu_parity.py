@@ -149,6 +149,90 @@ def test_select_on_device_importance_of_tiny_config():
     assert want["lengths"].sum() == w.budget_tokens()
 
 
+# ------------------------------------------------------------------- offline estimation (Sec. 3.3)
+@pytest.mark.parametrize("B,L,N,ties", [(1, 1, 1, False), (2, 4, 128, True), (3, 32, 680, False),
+                                        (2, 8, 8192, False), (1, 5, 1025, True)])
+def test_rank_bit_exact(B, L, N, ties):
+    imp = synthetic_importance(B, L, N, seed=77 + B + L + N, ties=ties)
+    got = P.prefixkv_rank(imp.to(DEV))
+    want = oracle.rank(imp.numpy())
+    np.testing.assert_array_equal(got.status.cpu().numpy(), want["status"])
+    np.testing.assert_array_equal(got.order.cpu().numpy(), want["order"])
+    np.testing.assert_array_equal(got.cum.cpu().numpy().view(np.uint64), want["cum"])
+    np.testing.assert_array_equal(got.prefix.cpu().numpy(), want["prefix"])
+    assert P.prefixkv_rank(imp.to(DEV), want_prefix=False).prefix is None
+
+
+def test_rank_status_words():
+    imp = synthetic_importance(5, 3, 50, seed=4)
+    imp[1, 2, 7] = float("nan")
+    imp[2, 1, 3] = -0.25
+    imp[3, 1, :] = 0.0
+    imp[4, 0, 3] = float("inf")
+    imp[4, 2, 5] = -1.0
+    got = P.prefixkv_rank(imp.to(DEV)).status.cpu().numpy()
+    want = oracle.rank(imp.numpy())["status"]
+    np.testing.assert_array_equal(got, want)
+    assert want.tolist() == [0, 1, 2, 4, 3]
+
+
+@pytest.mark.parametrize("S,L,N", [(1, 1, 1), (1, 4, 128), (10, 32, 680), (7, 40, 680), (3, 64, 8192),
+                                   (100, 5, 33)])
+def test_offline_config_bit_exact(S, L, N):
+    rng = np.random.default_rng(S * 100 + L + N)
+    total = L * N
+    for budget in sorted({1, L, L + 1, max(L + 1, total // 10), max(L + 1, total // 5), total - 1, total,
+                          total + 3}):
+        for kind in ("select", "random", "skewed", "zeros"):
+            if kind == "select":       # what the search really produces on S samples
+                imp = synthetic_importance(S, L, N, seed=S + L + N + budget % 97)
+                sl = oracle.select(imp.numpy(), min(budget, total))["lengths"]
+            elif kind == "random":
+                sl = rng.integers(0, N + 1, size=(S, L)).astype(np.int32)
+            elif kind == "skewed":     # one layer takes almost everything: clamps and the cyclic walk
+                sl = np.ones((S, L), np.int32)
+                sl[:, L // 2] = N
+            else:
+                sl = np.zeros((S, L), np.int32)
+            got = P.prefixkv_offline_config(torch.from_numpy(sl).to(DEV), N, budget, B_out=3).cpu().numpy()
+            want = oracle.offline_config(sl, N, budget)
+            np.testing.assert_array_equal(got, np.broadcast_to(want, (3, L)), err_msg=f"{kind} budget {budget}")
+
+
+def test_offline_pipeline_on_tiny_config():
+    """Calibrate on some sequences, deploy the shared configuration on others (Sec. 3.3, last
+    paragraph): rank each deployed sequence, compact with the shared lengths, decode."""
+    w = CONFIGS["tiny"]
+    x = make_prefill(w)
+    Bk = w.budget_tokens()
+    q, k, v, scale = (x[n].to(DEV) for n in ("q", "k", "v", "scale"))
+    imp = P.prefixkv_importance(q, k, scale)
+    cal = P.prefixkv_select(imp[:1].contiguous(), Bk)
+    shared = P.prefixkv_offline_config(cal.lengths, w.N, Bk, B_out=w.B)
+    rk = P.prefixkv_rank(imp)
+    steps = 3
+    tokens = P.prefixkv_cache_tokens_upper_bound(w.B, Bk, w.L, steps)
+    cache = P.prefixkv_compact(k, v, rk.order, shared, steps, tokens)
+    # oracle on the same importance tensor
+    impn = imp.cpu().numpy()
+    osel = oracle.select(impn[:1], Bk)
+    oshared = oracle.offline_config(osel["lengths"], w.N, Bk)
+    np.testing.assert_array_equal(shared.cpu().numpy(), np.broadcast_to(oshared, (w.B, w.L)))
+    assert oshared.sum() == Bk
+    orank = oracle.rank(impn)
+    olen = np.broadcast_to(oshared, (w.B, w.L)).copy()
+    ocache = oracle.compact(np32(x["k"]), np32(x["v"]), orank["order"], olen, steps)
+    dec = make_decode(w, steps=steps)
+    sc = x["scale"].numpy()
+    for t in range(steps):
+        out = P.prefixkv_decode_attn(cache, dec["q"][t].to(DEV), dec["k"][t].to(DEV), dec["v"][t].to(DEV),
+                                     scale, w.N)
+        ref = oracle.decode_attn(ocache, np32(dec["q"][t]), np32(dec["k"][t]), np32(dec["v"][t]), sc,
+                                 out_bf16=(w.dtype == "bf16"))
+        assert np.abs(np32(out) - ref).max() <= OUT_ATOL
+    np.testing.assert_array_equal(cache.lens.cpu().numpy(), olen + steps)
+
+
 # --------------------------------------------------------------------------------------- compaction
 def run_compact(k, v, sel, cap, budget):
     B, L = sel["lengths"].shape

@@ -457,3 +457,36 @@ def test_importance_row_restriction_keeps_tail_columns_exact():
     tail = oracle.importance(q, k, sc, m_lo=25)
     np.testing.assert_array_equal(tail[..., 25:], full[..., 25:])
     assert np.isnan(tail[..., :25]).all()
+
+
+# ----------------------------------------------------------------------------- offline configuration
+def test_offline_config_hand_example_and_invariants():
+    # two samples, three layers: totals (6, 3, 3) of 12; budget 8 of L*N = 3*10:
+    # 6*8/12 = 4 r0, 3*8/12 = 2 r0, 2 r0 -> exactly (4, 2, 2)
+    sl = np.array([[4, 1, 2], [2, 2, 1]], np.int32)
+    assert oracle.offline_config(sl, 10, 8).tolist() == [4, 2, 2]
+    # budget 10: 6*10/12 = 5 r0, 3*10/12 = 2 r6, 2 r6 -> one token missing, tie on the remainder -> lower layer
+    assert oracle.offline_config(sl, 10, 10).tolist() == [5, 3, 2]
+    # a single sample that already meets the budget is returned unchanged
+    one = np.array([[3, 5, 2]], np.int32)
+    assert oracle.offline_config(one, 10, 10).tolist() == [3, 5, 2]
+    # clamps
+    assert oracle.offline_config(sl, 10, 3).tolist() == [1, 1, 1]
+    assert oracle.offline_config(sl, 10, 30).tolist() == [10, 10, 10]
+    assert oracle.offline_config(np.zeros((2, 3), np.int32), 10, 8).tolist() == [0, 0, 0]
+    r = np.random.default_rng(3)
+    for _ in range(20):
+        S, L, N = int(r.integers(1, 6)), int(r.integers(2, 9)), int(r.integers(4, 50))
+        sl = r.integers(1, N + 1, (S, L)).astype(np.int32)
+        budget = int(r.integers(L + 1, L * N))
+        out = oracle.offline_config(sl, N, budget)
+        assert out.sum() == budget and out.min() >= 1 and out.max() <= N
+        # repeating the sample set does not change the configuration (ratios are averaged)
+        np.testing.assert_array_equal(oracle.offline_config(np.tile(sl, (3, 1)), N, budget), out)
+
+
+def test_rank_is_select_without_the_search():
+    imp = np.random.default_rng(4).random((2, 3, 17)).astype(np.float32)
+    a, b = oracle.rank(imp), oracle.select(imp, 20)
+    for k in ("order", "cum", "prefix", "status"):
+        np.testing.assert_array_equal(a[k], b[k])
