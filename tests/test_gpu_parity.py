@@ -183,6 +183,8 @@ def test_offline_config_bit_exact(S, L, N):
     total = L * N
     for budget in sorted({1, L, L + 1, max(L + 1, total // 10), max(L + 1, total // 5), total - 1, total,
                           total + 3}):
+        if budget < 1:
+            continue
         for kind in ("select", "random", "skewed", "zeros"):
             if kind == "select":       # what the search really produces on S samples
                 imp = synthetic_importance(S, L, N, seed=S + L + N + budget % 97)
