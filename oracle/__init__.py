@@ -43,6 +43,7 @@ def lib() -> C.CDLL:
         _lib.pkvo_threads.restype = C.c_int
         _lib.pkvo_decode_attn.restype = C.c_int
         _lib.pkvo_sort_prefix_layer.restype = C.c_int
+        _lib.pkvo_decode_attn_evict.restype = C.c_int
     return _lib
 
 
@@ -172,6 +173,28 @@ def decode_attn(cache, q, k_new, v_new, scale, l0=None, l1=None, out_bf16: bool 
                                 _p(cache["caps"]), _p(cache["lens"]), _p(out), int(out_bf16))
     if rc != 0:
         raise ValueError("append exceeds segment capacity")
+    return out
+
+
+def decode_attn_evict(cache, base_lens, q, k_new, v_new, scale, N: int, t: int, d: int, l0=None, l1=None,
+                      out_bf16: bool = False):
+    """Decode step t (1-based) with pruning at distance d on a cache dict from compact(); the cache
+    must have been built with decode_capacity >= d+1 (+ room for survivors).  base_lens [B,L] are the
+    prefill lengths.  Mutates kc/vc/kept_pos/lens (lens = permanent entries); returns out [B,L,H,D]."""
+    q, scale, k_new, v_new = _f32(q), _f32(scale), _f32(k_new), _f32(v_new)
+    B, L, H, D = q.shape
+    Hkv = cache["Hkv"]
+    l0 = 0 if l0 is None else l0
+    l1 = L if l1 is None else l1
+    base_lens = np.ascontiguousarray(base_lens, dtype=np.int32)
+    assert base_lens.shape == (B, L) and k_new.shape == (B, L, Hkv, D) and v_new.shape == (B, L, Hkv, D)
+    out = np.full((B, L, H, D), np.nan, np.float32)
+    rc = lib().pkvo_decode_attn_evict(B, L, H, Hkv, int(N), D, l0, l1, _p(q), _p(k_new), _p(v_new), _p(scale),
+                                      _p(cache["kc"]), _p(cache["vc"]), _p(cache["kept_pos"]),
+                                      _p(cache["seg_off"]), _p(cache["caps"]), _p(base_lens),
+                                      _p(cache["lens"]), int(t), int(d), _p(out), int(out_bf16))
+    if rc != 0:
+        raise ValueError("distance < 1, or the segment capacity cannot hold the ring and the survivors")
     return out
 
 

@@ -407,3 +407,113 @@ int pkvo_decode_attn(int B, int L, int H, int Hkv, int D, int l0, int l1, const 
         }
     return 0;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * Decode step with ratio maintenance (Sec. 3.1 last sentences and Fig. 3 caption: during decoding the
+ * vectors at a fixed distance to the latest generated token are pruned so that the global prefix
+ * configuration is maintained).  The paper gives neither the distance nor the bookkeeping; this reading:
+ *   - R_l = base_lens[b,l] / N is the layer's retention ratio found after prefill;
+ *   - after decode step t (1-based, sequence length N+t) the layer aims at
+ *       target(t) = max(1, round_half_up(R_l * (N+t))) cached entries;
+ *   - step t first stores the new token; then the token generated d steps earlier (token t-d, the one
+ *     at distance d from the newest) is decided once and for all: it stays for ever if the cache with
+ *     it is within the target, else it is pruned; for t <= d nothing is decided (the token at distance
+ *     d belongs to the prompt, whose selection the prefix configuration already made);
+ *   - the d newest tokens are always cached; the query of step t attends to the cache after pruning.
+ * Physical layout of a segment of `cap` slots: slots [0, lens) are the permanent entries (kept prompt
+ * positions, then survivors in the order they were decided), the LAST d+1 slots are a ring: token j sits
+ * in ring slot (j-1) mod (d+1), so the token decided in step t occupies the slot the next token will
+ * overwrite.  lens[b,l] counts permanent entries only.  kept_pos holds the sequence position of every
+ * live slot (prompt positions 0..N-1, decode token j at N+j-1), -1 for a pruned ring slot.
+ * Returns -1 (nothing modified) if d < 1, a ring does not fit behind the kept prompt entries, or a
+ * survivor would not fit in front of the ring.
+ * ------------------------------------------------------------------------------------------- */
+static int64_t pkvo_target(int64_t k_l, int64_t N, int64_t t) {
+    const int64_t r = (2 * k_l * (N + t) + N) / (2 * N);
+    return r < 1 ? 1 : r;
+}
+
+int pkvo_decode_attn_evict(int B, int L, int H, int Hkv, int N, int D, int l0, int l1, const float *q,
+                           const float *k_new, const float *v_new, const float *scale, float *kc,
+                           float *vc, int32_t *kept_pos, const int64_t *seg_off, const int32_t *caps,
+                           const int32_t *base_lens, int32_t *lens, int t, int d, float *out,
+                           int out_bf16) {
+    const int grp = H / Hkv;
+    if (d < 1 || t < 1) return -1;
+    for (int b = 0; b < B; ++b)
+        for (int l = l0; l < l1; ++l) {
+            const long bl = (long)b * L + l;
+            const int ring0 = caps[bl] - (d + 1);
+            if (ring0 < base_lens[bl] || lens[bl] > ring0) return -1;
+            if (t > d && lens[bl] + d + 1 <= pkvo_target(base_lens[bl], N, t) && lens[bl] >= ring0) return -1;
+        }
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+    for (int b = 0; b < B; ++b)
+        for (int l = l0; l < l1; ++l) {
+            const long bl = (long)b * L + l;
+            const int cap = caps[bl];
+            const int ring0 = cap - (d + 1);
+            int perm = lens[bl];
+            int32_t *kp = kept_pos + seg_off[bl];
+            /* 1. store token t in its ring slot */
+            const int ns = ring0 + (t - 1) % (d + 1);
+            for (int h = 0; h < Hkv; ++h) {
+                const size_t dst = ((size_t)seg_off[bl] * Hkv + (size_t)h * cap + ns) * D;
+                memcpy(kc + dst, k_new + ((size_t)bl * Hkv + h) * D, sizeof(float) * (size_t)D);
+                memcpy(vc + dst, v_new + ((size_t)bl * Hkv + h) * D, sizeof(float) * (size_t)D);
+            }
+            kp[ns] = N + t - 1;
+            /* 2. decide token t-d */
+            if (t > d) {
+                const int cs = ring0 + t % (d + 1);
+                if (perm + d + 1 <= pkvo_target(base_lens[bl], N, t)) {
+                    for (int h = 0; h < Hkv; ++h) {
+                        const size_t sb = ((size_t)seg_off[bl] * Hkv + (size_t)h * cap) * D;
+                        memcpy(kc + sb + (size_t)perm * D, kc + sb + (size_t)cs * D, sizeof(float) * (size_t)D);
+                        memcpy(vc + sb + (size_t)perm * D, vc + sb + (size_t)cs * D, sizeof(float) * (size_t)D);
+                    }
+                    kp[perm] = kp[cs];
+                    perm += 1;
+                }
+                /* survivor or not, the ring slot no longer holds a cached entry */
+                for (int h = 0; h < Hkv; ++h) {
+                    const size_t sb = ((size_t)seg_off[bl] * Hkv + (size_t)h * cap + cs) * D;
+                    for (int x = 0; x < D; ++x) { kc[sb + x] = NAN; vc[sb + x] = NAN; }
+                }
+                kp[cs] = -1;
+                lens[bl] = perm;
+            }
+            /* 3. attention of the new query over the live slots: permanent entries, then ring */
+            int *slot = (int *)malloc(sizeof(int) * (size_t)(perm + d + 1));
+            int n = 0;
+            for (int j = 0; j < perm; ++j) slot[n++] = j;
+            for (int j = 0; j <= d; ++j)
+                if (kp[ring0 + j] >= N + t - d && kp[ring0 + j] <= N + t - 1) slot[n++] = ring0 + j;
+            double *s = (double *)malloc(sizeof(double) * (size_t)n);
+            for (int h = 0; h < H; ++h) {
+                const float *qh = q + ((size_t)bl * H + h) * D;
+                const size_t base = ((size_t)seg_off[bl] * Hkv + (size_t)(h / grp) * cap) * D;
+                float *oh = out + ((size_t)bl * H + h) * D;
+                double mx = -INFINITY;
+                for (int j = 0; j < n; ++j) {
+                    double dot = 0.0;
+                    for (int x = 0; x < D; ++x)
+                        dot += (double)qh[x] * (double)kc[base + (size_t)slot[j] * D + x];
+                    s[j] = (double)scale[l] * dot;
+                    if (s[j] > mx) mx = s[j];
+                }
+                double den = 0.0;
+                for (int j = 0; j < n; ++j) { s[j] = exp(s[j] - mx); den += s[j]; }
+                for (int x = 0; x < D; ++x) {
+                    double acc = 0.0;
+                    for (int j = 0; j < n; ++j)
+                        acc += s[j] * (double)vc[base + (size_t)slot[j] * D + x];
+                    acc /= den;
+                    oh[x] = out_bf16 ? pkvo_round_bf16(acc) : (float)acc;
+                }
+            }
+            free(s);
+            free(slot);
+        }
+    return 0;
+}

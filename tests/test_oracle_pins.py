@@ -490,3 +490,135 @@ def test_rank_is_select_without_the_search():
     a, b = oracle.rank(imp), oracle.select(imp, 20)
     for k in ("order", "cum", "prefix", "status"):
         np.testing.assert_array_equal(a[k], b[k])
+
+
+# ------------------------------------------------------ decode-time pruning at a fixed distance
+def run_evict(seed, lengths, N, d, T, Hkv=2, H=4, D=8, extra=None):
+    """Build a cache with the given per-layer lengths (B = 1) and run T pruning decode steps.
+    Returns per-step outputs and the inputs, plus the state after each step."""
+    r = np.random.default_rng(seed)
+    lengths = np.asarray(lengths, np.int32)[None]
+    L = lengths.shape[1]
+    k = r.standard_normal((1, L, Hkv, N, D)).astype(np.float32)
+    v = r.standard_normal((1, L, Hkv, N, D)).astype(np.float32)
+    order = np.stack([r.permutation(N) for _ in range(L)])[None].astype(np.int32)
+    cap = d + 1 + (T if extra is None else extra)
+    cache = oracle.compact(k, v, order, lengths, cap)
+    sc = r.uniform(0.1, 1, L).astype(np.float32)
+    q = r.standard_normal((T, 1, L, H, D)).astype(np.float32)
+    kn = r.standard_normal((T, 1, L, Hkv, D)).astype(np.float32)
+    vn = r.standard_normal((T, 1, L, Hkv, D)).astype(np.float32)
+    outs, states = [], []
+    for t in range(1, T + 1):
+        outs.append(oracle.decode_attn_evict(cache, lengths, q[t - 1], kn[t - 1], vn[t - 1], sc, N, t, d))
+        states.append([(int(cache["lens"][0, l]), oracle.segment(cache, "kept_pos", 0, l).copy())
+                       for l in range(L)])
+    return dict(k=k, v=v, order=order, lengths=lengths, sc=sc, q=q, kn=kn, vn=vn, outs=outs, states=states,
+                cache=cache)
+
+
+def test_evict_hand_trace(golden_dir):
+    g = json.load(open(os.path.join(golden_dir, "evict_hand_trace.json")))
+    N, d, T = g["N"], g["d"], len(g["target"])
+    x = run_evict(31, [g["base_len"]], N, d, T)
+    for t in range(1, T + 1):
+        perm, kp = x["states"][t - 1][0]
+        assert perm == g["permanent_after_step"][t - 1]
+        live = sorted(int(p) - N + 1 for p in kp if p >= N)
+        assert live == g["live_decode_tokens_after_step"][t - 1]
+        assert perm + min(t, d) == max(g["target"][t - 1], g["base_len"] + min(t, d))
+
+
+@pytest.mark.parametrize("seed,N,d,T", [(1, 16, 1, 40), (2, 16, 3, 60), (3, 33, 8, 120), (4, 7, 2, 50)])
+def test_evict_cache_size_closed_form_and_set_invariants(seed, N, d, T):
+    """Because the target grows by at most one entry per step, the rule has a closed form: the cache holds
+    max(target(t), k_l + min(t, d)) entries after step t.  Besides: the d newest tokens are always live,
+    kept prompt entries never leave, a pruned token never returns, survivors keep their decision order,
+    and every live slot holds the K/V rows of the position it is labelled with."""
+    r = np.random.default_rng(seed)
+    L = 5
+    lengths = np.concatenate([[0, 1, N], r.integers(1, N + 1, L - 3)])
+    x = run_evict(seed + 100, lengths, N, d, T)
+    from fractions import Fraction
+    for l in range(L):
+        kl = int(lengths[l])
+        prev_live = None
+        for t in range(1, T + 1):
+            perm, kp = x["states"][t - 1][l]
+            tgt = max(1, int(Fraction(kl * (N + t), N) + Fraction(1, 2)))     # round half up, exactly
+            live = [int(p) for p in kp if p >= 0]
+            assert len(live) == len(set(live)) == perm + min(t, d) == max(tgt, kl + min(t, d))
+            assert set(range(N + t - min(t, d), N + t)) <= set(live)            # the d newest
+            assert set(np.sort(x["order"][0, l, :kl]).tolist()) == {p for p in live if p < N}
+            assert list(kp[:kl]) == sorted(kp[:kl]) and list(kp[kl:perm]) == sorted(kp[kl:perm])
+            if prev_live is not None:
+                gone = prev_live - set(live)
+                assert len(gone) <= 1 and all(p == N + t - d - 1 for p in gone)  # only the decided token
+                assert set(live) - prev_live <= {N + t - 1} | set()              # only the new token enters
+            prev_live = set(live)
+            if t == T:
+                K = oracle.segment(x["cache"], "kc", 0, l)
+                V = oracle.segment(x["cache"], "vc", 0, l)
+                for slot, p in enumerate(kp):
+                    if p < 0:
+                        continue
+                    wk = x["k"][0, l, :, p] if p < N else x["kn"][p - N, 0, l]
+                    wv = x["v"][0, l, :, p] if p < N else x["vn"][p - N, 0, l]
+                    np.testing.assert_array_equal(K[:, slot], wk)
+                    np.testing.assert_array_equal(V[:, slot], wv)
+
+
+def test_evict_distance_beyond_horizon_is_plain_append():
+    """d >= T: nothing is ever decided, so every step equals the append-only decode step."""
+    N, T, d = 12, 5, 9
+    x = run_evict(41, [3, 7, 12], N, d, T)
+    cache = oracle.compact(x["k"], x["v"], x["order"], x["lengths"], T)
+    for t in range(T):
+        want = oracle.decode_attn(cache, x["q"][t], x["kn"][t], x["vn"][t], x["sc"])
+        np.testing.assert_array_equal(x["outs"][t], want)
+
+
+def attention_over_positions(x, l, t, positions):
+    """Dense softmax attention of step t's query over an explicit list of sequence positions."""
+    N = x["k"].shape[3]
+    K = np.stack([x["k"][0, l, :, p] if p < N else x["kn"][p - N, 0, l] for p in positions], 1)
+    V = np.stack([x["v"][0, l, :, p] if p < N else x["vn"][p - N, 0, l] for p in positions], 1)
+    H = x["q"].shape[3]
+    rep = H // K.shape[0]
+    return dense_attention(x["q"][t - 1, 0, l].astype(np.float64), np.repeat(K, rep, 0).astype(np.float64),
+                           np.repeat(V, rep, 0).astype(np.float64), float(x["sc"][l]))
+
+
+def test_evict_full_ratio_keeps_everything_and_tiny_ratio_is_a_sliding_window():
+    """R_l = 1: every decided token survives -> full-cache attention over prompt + all decode tokens.
+    One kept prompt entry of a long prompt: the target stays at 1, every decided token is pruned ->
+    attention over that entry plus a sliding window of the d newest tokens."""
+    N, d, T = 40, 3, 12
+    x = run_evict(51, [N, 1], N, d, T)
+    sink = int(x["order"][0, 1, 0])
+    for t in range(1, T + 1):
+        full = attention_over_positions(x, 0, t, list(range(N + t)))
+        np.testing.assert_allclose(x["outs"][t - 1][0, 0], full, rtol=1e-5, atol=1e-6)
+        window = [sink] + list(range(N + t - min(t, d), N + t))
+        np.testing.assert_allclose(x["outs"][t - 1][0, 1], attention_over_positions(x, 1, t, window),
+                                   rtol=1e-5, atol=1e-6)
+
+
+def test_evict_general_case_attends_to_exactly_the_live_set():
+    N, d, T = 24, 4, 40
+    x = run_evict(61, [6, 13, 20], N, d, T)
+    for l in range(3):
+        for t in (1, 4, 5, 17, 40):
+            _, kp = x["states"][t - 1][l]
+            live = [int(p) for p in kp if p >= 0]
+            np.testing.assert_allclose(x["outs"][t - 1][0, l], attention_over_positions(x, l, t, live),
+                                       rtol=1e-5, atol=1e-6)
+
+
+def test_evict_refuses_bad_capacity_or_distance():
+    with pytest.raises(ValueError):
+        run_evict(71, [3], 8, 0, 2)                 # distance 0 would decide the token being stored
+    with pytest.raises(ValueError):
+        run_evict(72, [8], 8, 2, 6, extra=1)        # survivors do not fit in front of the ring
+    x = run_evict(73, [3], 8, 2, 6, extra=0)        # R small enough that nothing survives in 6 steps
+    assert x["states"][-1][0][0] == 3
