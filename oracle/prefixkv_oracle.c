@@ -488,7 +488,7 @@ int pkvo_decode_attn_evict(int B, int L, int H, int Hkv, int N, int D, int l0, i
             int n = 0;
             for (int j = 0; j < perm; ++j) slot[n++] = j;
             for (int j = 0; j <= d; ++j)
-                if (kp[ring0 + j] >= N + t - d && kp[ring0 + j] <= N + t - 1) slot[n++] = ring0 + j;
+                if (kp[ring0 + j] >= 0) slot[n++] = ring0 + j; /* stored and not yet decided */
             double *s = (double *)malloc(sizeof(double) * (size_t)n);
             for (int h = 0; h < H; ++h) {
                 const float *qh = q + ((size_t)bl * H + h) * D;

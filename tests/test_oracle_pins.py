@@ -570,12 +570,12 @@ def test_evict_cache_size_closed_form_and_set_invariants(seed, N, d, T):
 
 def test_evict_distance_beyond_horizon_is_plain_append():
     """d >= T: nothing is ever decided, so every step equals the append-only decode step."""
-    N, T, d = 12, 5, 9
-    x = run_evict(41, [3, 7, 12], N, d, T)
-    cache = oracle.compact(x["k"], x["v"], x["order"], x["lengths"], T)
-    for t in range(T):
-        want = oracle.decode_attn(cache, x["q"][t], x["kn"][t], x["vn"][t], x["sc"])
-        np.testing.assert_array_equal(x["outs"][t], want)
+    for N, T, d in ((12, 5, 9), (12, 5, 20)):       # also a distance longer than the prompt
+        x = run_evict(41, [3, 7, 12], N, d, T)
+        cache = oracle.compact(x["k"], x["v"], x["order"], x["lengths"], T)
+        for t in range(T):
+            want = oracle.decode_attn(cache, x["q"][t], x["kn"][t], x["vn"][t], x["sc"])
+            np.testing.assert_array_equal(x["outs"][t], want)
 
 
 def attention_over_positions(x, l, t, positions):
