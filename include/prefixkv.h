@@ -181,6 +181,39 @@ int prefixkv_decode_attn(const pkv_shape *shape, int l0, int l1, const void *q, 
                          const int64_t *seg_off, const int32_t *caps, int32_t *lens, void *out,
                          void *ws, size_t ws_bytes, pkv_stream stream);
 
+/* ---- Decode step with ratio maintenance (Sec. 3.1, last sentences, and the caption of Fig. 3:
+ * while decoding, the vectors at a fixed distance to the latest generated token are pruned so that
+ * the prefix configuration found after prefill keeps holding).  The paper states neither the
+ * distance nor the bookkeeping; this library's reading:
+ *   R_l = base_lens[b,l] / N;  after decode step t (1-based; the sequence then has N+t tokens) the
+ *   segment aims at  target(t) = max(1, floor((2*base_lens*(N+t) + N) / (2N)))  entries
+ *   (= R_l*(N+t) rounded half up).  Step t stores the new token, then decides the token stored
+ *   `distance` steps earlier, once: it becomes a permanent entry if the cache including it is within
+ *   target(t), else it is dropped.  Steps t <= distance decide nothing.  The `distance` newest tokens
+ *   are always cached.  The query of step t attends to the cache AFTER this decision.  The number of
+ *   cached entries after step t is max(target(t), base_lens + min(t, distance)).
+ * Segment layout: slots [0, lens) are permanent entries (the kept prompt positions from
+ * prefixkv_compact, then survivors in the order they were decided); the LAST distance+1 slots of
+ * the segment (caps - distance - 1 ... caps - 1) are a ring, decode token j in ring slot
+ * (j-1) mod (distance+1).  lens[b,l] counts PERMANENT entries only and must come from
+ * prefixkv_compact (t = 1) or the previous call (t-1) with the same distance; a cache driven through
+ * this entry point must not be passed to prefixkv_decode_attn.  prefixkv_compact must have been
+ * called with decode_capacity >= distance+1 + the number of survivors the caller will allow
+ * (never more than the number of steps).  A segment whose capacity cannot hold the ring behind its
+ * kept prompt entries is left untouched and outputs zeros; a survivor that does not fit in front of
+ * the ring is dropped.
+ *   base_lens [dev] i32 [B,L]: the `lengths` given to prefixkv_compact (read only)
+ *   kept_pos  [dev] i32 or NULL: if given, slot labels are maintained: N+j-1 for decode token j in the
+ *       ring and in the permanent region, -1 for a ring slot whose token was decided
+ *   t: 1-based decode step since prefixkv_compact;  1 <= distance <= 65535
+ * Everything else as in prefixkv_decode_attn (k_new, v_new required). */
+int prefixkv_decode_attn_evict(const pkv_shape *shape, int l0, int l1, const void *q,
+                               const void *k_new, const void *v_new, const float *scale, void *kc,
+                               void *vc, const int64_t *seg_off, const int32_t *caps,
+                               const int32_t *base_lens, int32_t *lens, int32_t *kept_pos, int t,
+                               int distance, void *out, void *ws, size_t ws_bytes,
+                               pkv_stream stream);
+
 /* Measurement aid, not part of the method: a plain device-to-device copy kernel of a known size
  * (bytes % 16 == 0, 16-byte aligned pointers).  It reads `bytes` and writes `bytes`, which is what
  * hardware byte counters are calibrated against when a kernel's HBM traffic is reported. */

@@ -81,6 +81,9 @@ def load(path: Optional[str] = None) -> C.CDLL:
     L.prefixkv_decode_attn.restype = C.c_int
     L.prefixkv_decode_attn.argtypes = [C.POINTER(_Shape), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                        vp, sz, vp]
+    L.prefixkv_decode_attn_evict.restype = C.c_int
+    L.prefixkv_decode_attn_evict.argtypes = [C.POINTER(_Shape), i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                             vp, vp, i32, i32, vp, vp, sz, vp]
     L.prefixkv_calibration_copy.restype = C.c_int
     L.prefixkv_calibration_copy.argtypes = [vp, vp, sz, vp]
     _lib = L
@@ -330,6 +333,36 @@ def prefixkv_decode_attn(cache: CompactResult, q: torch.Tensor, k_new: Optional[
                                      _ptr(cache.caps), _ptr(cache.lens), _ptr(out), None, 0, _stream())
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_decode_attn")
+    return out
+
+
+def prefixkv_decode_attn_evict(cache: CompactResult, base_lens: torch.Tensor, q: torch.Tensor,
+                               k_new: torch.Tensor, v_new: torch.Tensor, scale: torch.Tensor, N: int, t: int,
+                               distance: int, l0: int = 0, l1: Optional[int] = None,
+                               track_positions: bool = True, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Decode step t (1-based) with pruning at `distance` from the newest token; cache.lens counts the
+    permanent entries.  base_lens [B,L] i32 = the lengths the cache was compacted with."""
+    _need_cuda(q, k_new, v_new, scale, base_lens, out)
+    B, L, H, D = q.shape
+    l1 = L if l1 is None else l1
+    if not q.is_contiguous() or q.dtype != cache.kc.dtype or D != cache.D:
+        raise ValueError("q must be contiguous [B,L,H,D] in the cache dtype")
+    for x in (k_new, v_new):
+        if x.shape != (B, L, cache.Hkv, D) or not x.is_contiguous() or x.dtype != q.dtype:
+            raise ValueError("k_new/v_new must be contiguous [B,L,Hkv,D] in the cache dtype")
+    if scale.dtype != torch.float32 or scale.shape != (L,) or not scale.is_contiguous():
+        raise ValueError("scale must be contiguous f32 [L]")
+    if base_lens.dtype != torch.int32 or base_lens.shape != (B, L) or not base_lens.is_contiguous():
+        raise ValueError("base_lens must be contiguous i32 [B,L]")
+    if out is None:
+        out = torch.empty((B, L, H, D), dtype=q.dtype, device=q.device)
+    s = _shape(B, L, H, cache.Hkv, N, D, _dtype_code(q))
+    rc = load().prefixkv_decode_attn_evict(
+        C.byref(s), int(l0), int(l1), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(scale), _ptr(cache.kc),
+        _ptr(cache.vc), _ptr(cache.seg_off), _ptr(cache.caps), _ptr(base_lens), _ptr(cache.lens),
+        _ptr(cache.kept_pos) if track_positions else None, int(t), int(distance), _ptr(out), None, 0, _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_decode_attn_evict")
     return out
 
 

@@ -148,6 +148,25 @@ int prefixkv_decode_attn(const pkv_shape* s, int l0, int l1, const void* q, cons
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
 
+int prefixkv_decode_attn_evict(const pkv_shape* s, int l0, int l1, const void* q, const void* k_new,
+                               const void* v_new, const float* scale, void* kc, void* vc,
+                               const int64_t* seg_off, const int32_t* caps, const int32_t* base_lens,
+                               int32_t* lens, int32_t* kept_pos, int t, int distance, void* out, void* ws,
+                               size_t ws_bytes, pkv_stream stream) {
+    if (!s || !q || !k_new || !v_new || !scale || !kc || !vc || !seg_off || !caps || !base_lens || !lens || !out)
+        return PKV_ERR_NULL;
+    if (!shape_ok(s) || l0 < 0 || l1 > s->L || l0 >= l1 || s->H > 2048) return PKV_ERR_DIM;
+    if (t < 1 || t > (1 << 30) || distance < 1 || distance > 65535) return PKV_ERR_DIM;
+    if (!dtype_ok(s)) return PKV_ERR_DTYPE;
+    if (!aligned16(q) || !aligned16(kc) || !aligned16(vc) || !aligned16(out) || !aligned16(k_new) ||
+        !aligned16(v_new))
+        return PKV_ERR_STRIDE;
+    (void)ws; (void)ws_bytes;  // this stage needs no scratch
+    const hipError_t e = launch_decode_evict(*s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, base_lens,
+                                             lens, kept_pos, t, distance, out, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
 int prefixkv_calibration_copy(void* dst, const void* src, size_t bytes, pkv_stream stream) {
     if (!dst || !src) return PKV_ERR_NULL;
     if (bytes == 0 || bytes % 16 != 0) return PKV_ERR_DIM;

@@ -37,6 +37,19 @@ struct DecodeParams {
     const int32_t* caps;          // [B,L]
     int32_t* lens;                // [B,L]
     unsigned char* out;           // [B,L,H,D]
+    // pruning at a fixed distance (decode_attn_kernel<..., EV = true> only)
+    int N, t, d;                  // prompt length, 1-based decode step, distance
+    const int32_t* base_lens;     // [B,L] entries kept after prefill
+    int32_t* kept_pos;            // one int per slot, may be null
+};
+
+// Virtual row numbering of a segment under pruning: rows [0, perm) are the permanent slots, rows
+// perm + j are ring slot j (the last d+1 slots of the segment).  r_new is the row of the token stored
+// in this step, r_mask the row of a token pruned in this step (-1 if none).
+struct RingMap {
+    int shift;    // ring slot j is physical slot perm + j + shift
+    int r_new;
+    int r_mask;
 };
 
 // Cache rows are read once per decode step and never reused by the same launch: stream them past the
@@ -64,10 +77,10 @@ __device__ __forceinline__ void unpack16(const uint4& r, float* f) {
 // the group: online-softmax update of (mrun, srun, o).  LPR lanes cover one row with 16 bytes each.
 // TAIL = false: every row is an occupied cache slot.  TAIL = true: rows >= len are masked, and the row
 // len_old, if it is being appended (app), comes from k_new/v_new and is written to its slot (writer).
-template <bool BF16, int LPR, int G, int NI, bool TAIL>
+template <bool BF16, int LPR, int G, int NI, bool TAIL, bool EV = false>
 __device__ __forceinline__ void attend_block(const unsigned char* __restrict__ kseg,
                                              const unsigned char* __restrict__ vseg, int r0, int len,
-                                             int len_old, bool app, bool writer,
+                                             int len_old, bool app, bool writer, const RingMap& ring,
                                              const unsigned char* __restrict__ knew,
                                              const unsigned char* __restrict__ vnew, unsigned char* kw,
                                              unsigned char* vw, int row_bytes, int sub, int rg,
@@ -86,13 +99,26 @@ __device__ __forceinline__ void attend_block(const unsigned char* __restrict__ k
         } else {
             const int r = r0 + i * RPI + rg;
             kr[i] = make_uint4(0, 0, 0, 0); vr[i] = make_uint4(0, 0, 0, 0);
-            if (r < len) {
-                const bool isnew = app && r == len_old;
-                kr[i] = load_stream16(isnew ? knew + sub * 16 : kseg + o_i);
-                vr[i] = load_stream16(isnew ? vnew + sub * 16 : vseg + o_i);
-                if (isnew && writer) {
-                    *(uint4*)(kw + o_i) = kr[i];
-                    *(uint4*)(vw + o_i) = vr[i];
+            if constexpr (!EV) {
+                if (r < len) {
+                    const bool isnew = app && r == len_old;
+                    kr[i] = load_stream16(isnew ? knew + sub * 16 : kseg + o_i);
+                    vr[i] = load_stream16(isnew ? vnew + sub * 16 : vseg + o_i);
+                    if (isnew && writer) {
+                        *(uint4*)(kw + o_i) = kr[i];
+                        *(uint4*)(vw + o_i) = vr[i];
+                    }
+                }
+            } else {
+                if (r < len && r != ring.r_mask) {
+                    const uint32_t o_s = o_i + (r >= len_old ? (uint32_t)ring.shift * (uint32_t)row_bytes : 0u);
+                    const bool isnew = r == ring.r_new;
+                    kr[i] = load_stream16(isnew ? knew + sub * 16 : kseg + o_s);
+                    vr[i] = load_stream16(isnew ? vnew + sub * 16 : vseg + o_s);
+                    if (isnew && writer) {
+                        *(uint4*)(kw + o_s) = kr[i];
+                        *(uint4*)(vw + o_s) = vr[i];
+                    }
                 }
             }
         }
@@ -111,7 +137,10 @@ __device__ __forceinline__ void attend_block(const unsigned char* __restrict__ k
             for (int x = 0; x < EPL; ++x) d = fmaf(qf[g][x], kf[x], d);
 #pragma unroll
             for (int sh = 1; sh < LPR; sh <<= 1) d += __shfl_xor(d, sh, kWave);
-            if constexpr (TAIL) d = (r0 + i * RPI + rg < len) ? d : -INFINITY;
+            if constexpr (TAIL) {
+                const int r = r0 + i * RPI + rg;
+                d = (r < len && (!EV || r != ring.r_mask)) ? d : -INFINITY;
+            }
             s[g][i] = d;
             mx[g] = fmaxf(mx[g], d);
         }
@@ -143,7 +172,7 @@ __device__ __forceinline__ void attend_block(const unsigned char* __restrict__ k
 }
 
 // W wavefronts per workgroup; OCC = wavefronts per SIMD the register allocation must allow.
-template <bool BF16, int LPR, int G, int NI, int W, int OCC>
+template <bool BF16, int LPR, int G, int NI, int W, int OCC, bool EV = false>
 __global__ void __launch_bounds__(W * kWave, OCC)
 decode_attn_kernel(DecodeParams p) {
     constexpr int EPL = BF16 ? 8 : 4;            // elements per lane (16 bytes)
@@ -165,8 +194,29 @@ decode_attn_kernel(DecodeParams p) {
     const int len_old = __hip_atomic_load(p.lens + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kLenMask;
     const int cap = p.caps[sl];
     const int64_t off = p.seg_off[sl];
-    const bool app = p.append && len_old < cap;
-    const int len = len_old + (app ? 1 : 0);
+    // plain step: append at slot len_old.  Pruning step: len_old counts the permanent entries, the new
+    // token goes to ring slot (t-1) mod (d+1), and the token stored d steps ago (ring slot t mod (d+1))
+    // either becomes permanent entry len_old or is left out from now on.
+    bool app = p.append && len_old < cap;
+    int len = len_old + (app ? 1 : 0), len_next = len;
+    RingMap ring = {0, -1, -1};
+    int ring0 = 0, cs = 0;
+    bool grad = false, decide = false;
+    if constexpr (EV) {
+        const int base = p.base_lens[sl];
+        ring0 = cap - (p.d + 1);
+        app = base >= 0 && ring0 >= base && len_old <= ring0;   // else: capacity cannot hold the ring
+        decide = app && p.t > p.d;
+        cs = p.t % (p.d + 1);
+        long long target = (2ll * base * ((long long)p.N + p.t) + p.N) / (2ll * p.N);
+        target = target < 1 ? 1 : target;
+        grad = decide && (long long)len_old + p.d + 1 <= target && len_old < ring0;
+        ring.shift = ring0 - len_old;
+        ring.r_new = len_old + (p.t - 1) % (p.d + 1);
+        ring.r_mask = (decide && !grad) ? len_old + cs : -1;
+        len = app ? len_old + (p.t < p.d + 1 ? p.t : p.d + 1) : 0;
+        len_next = len_old + (grad ? 1 : 0);
+    }
     const int nch = (len + kDecodeChunk - 1) / kDecodeChunk;
     const int kvh = (hu * G) / p.grp;
     const bool writer = app && ((hu * G) % p.grp == 0);
@@ -199,12 +249,17 @@ decode_attn_kernel(DecodeParams p) {
             for (int sb = 0; sb < NSB; ++sb) {
                 const int r0 = c * kDecodeChunk + sb * SB;
                 if (full) {
-                    attend_block<BF16, LPR, G, NI, false>(kseg, vseg, r0, len, len_old, app, writer, nullptr, nullptr,
-                                                          nullptr, nullptr, row_bytes, sub, rg, qf, o, mrun, srun);
+                    attend_block<BF16, LPR, G, NI, false>(kseg, vseg, r0, len, len_old, app, writer, ring, nullptr,
+                                                          nullptr, nullptr, nullptr, row_bytes, sub, rg, qf, o,
+                                                          mrun, srun);
                 } else if (r0 < len) {
-                    attend_block<BF16, LPR, G, NI, true>(kseg, vseg, r0, len, len_old, app, writer,
-                                                         p.k_new + newrow, p.v_new + newrow, p.kc + segbase,
-                                                         p.vc + segbase, row_bytes, sub, rg, qf, o, mrun, srun);
+                    if constexpr (EV) {   // a sub-block whose only occupied row is the pruned one has no work
+                        const int hi = len < r0 + SB ? len : r0 + SB;
+                        if (hi - r0 == 1 && ring.r_mask == r0) continue;
+                    }
+                    attend_block<BF16, LPR, G, NI, true, EV>(kseg, vseg, r0, len, len_old, app, writer, ring,
+                                                             p.k_new + newrow, p.v_new + newrow, p.kc + segbase,
+                                                             p.vc + segbase, row_bytes, sub, rg, qf, o, mrun, srun);
                 }
             }
         }
@@ -216,6 +271,24 @@ decode_attn_kernel(DecodeParams p) {
                 srun[g] += __shfl_xor(srun[g], sh, kWave);
 #pragma unroll
                 for (int x = 0; x < EPL; ++x) o[g][x] += __shfl_xor(o[g][x], sh, kWave);
+            }
+        }
+    }
+    if constexpr (EV) {
+        // the surviving token moves from its ring slot to the next permanent slot.  Attention above read it
+        // from the ring slot; nobody reads the permanent slot in this launch.
+        if (grad && writer && wv == 0 && rg == 0) {
+            const unsigned char* src_k = p.kc + segbase + (size_t)(ring0 + cs) * row_bytes + sub * 16;
+            const unsigned char* src_v = p.vc + segbase + (size_t)(ring0 + cs) * row_bytes + sub * 16;
+            *(uint4*)(p.kc + segbase + (size_t)len_old * row_bytes + sub * 16) = *(const uint4*)src_k;
+            *(uint4*)(p.vc + segbase + (size_t)len_old * row_bytes + sub * 16) = *(const uint4*)src_v;
+        }
+        if (p.kept_pos && app && hu == 0 && threadIdx.x == 0) {
+            int32_t* kp = p.kept_pos + off;
+            kp[ring0 + (p.t - 1) % (p.d + 1)] = p.N + p.t - 1;
+            if (decide) {
+                if (grad) kp[len_old] = p.N + p.t - p.d - 1;
+                kp[ring0 + cs] = -1;
             }
         }
     }
@@ -252,7 +325,7 @@ decode_attn_kernel(DecodeParams p) {
     if (threadIdx.x == 0) {
         const int old = atomicAdd(p.lens + sl, 1 << kLenBits);
         if ((int)((unsigned)old >> kLenBits) == HU - 1)
-            __hip_atomic_store(p.lens + sl, len, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.lens + sl, len_next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -267,7 +340,7 @@ static int pick_group(int grp) { return grp % 8 == 0 ? 8 : grp % 4 == 0 ? 4 : gr
 //   shape 1: 4 wavefronts,  8 loads in flight, 4 wavefronts/SIMD   (up to ~4k tokens)
 //   shape 2: 8 wavefronts,  8 loads in flight, 4 wavefronts/SIMD   (longer)
 // Groups of 4 or 8 query heads keep 8 loads in flight and 2 wavefronts/SIMD (register budget).
-template <bool BF16, int LPR, int G>
+template <bool BF16, int LPR, int G, bool EV>
 static hipError_t launch_decode_s(const DecodeParams& p, int shape, int nblk, hipStream_t st) {
     constexpr int RPI = kWave / LPR;
     constexpr int NI_MAX = kDecodeChunk / RPI;
@@ -276,28 +349,42 @@ static hipError_t launch_decode_s(const DecodeParams& p, int shape, int nblk, hi
     constexpr int NI8 = NI_MAX < 8 ? NI_MAX : 8;
     constexpr int OCC4 = WIDE ? 2 : 4;
     if (shape == 0)
-        hipLaunchKernelGGL((decode_attn_kernel<BF16, LPR, G, NI16, 2, 2>), dim3(nblk), dim3(2 * kWave), 0, st, p);
+        hipLaunchKernelGGL((decode_attn_kernel<BF16, LPR, G, NI16, 2, 2, EV>), dim3(nblk), dim3(2 * kWave), 0, st, p);
     else if (shape == 1)
-        hipLaunchKernelGGL((decode_attn_kernel<BF16, LPR, G, NI8, 4, OCC4>), dim3(nblk), dim3(4 * kWave), 0, st, p);
+        hipLaunchKernelGGL((decode_attn_kernel<BF16, LPR, G, NI8, 4, OCC4, EV>), dim3(nblk), dim3(4 * kWave), 0, st, p);
     else
-        hipLaunchKernelGGL((decode_attn_kernel<BF16, LPR, G, NI8, 8, OCC4>), dim3(nblk), dim3(8 * kWave), 0, st, p);
+        hipLaunchKernelGGL((decode_attn_kernel<BF16, LPR, G, NI8, 8, OCC4, EV>), dim3(nblk), dim3(8 * kWave), 0, st, p);
     return hipGetLastError();
 }
 
-template <bool BF16, int LPR>
+template <bool BF16, int LPR, bool EV>
 static hipError_t launch_decode_g(const DecodeParams& p, int G, int shape, int nblk, hipStream_t st) {
     switch (G) {
-        case 8: return launch_decode_s<BF16, LPR, 8>(p, shape, nblk, st);
-        case 4: return launch_decode_s<BF16, LPR, 4>(p, shape, nblk, st);
-        case 2: return launch_decode_s<BF16, LPR, 2>(p, shape, nblk, st);
-        default: return launch_decode_s<BF16, LPR, 1>(p, shape, nblk, st);
+        case 8: return launch_decode_s<BF16, LPR, 8, EV>(p, shape, nblk, st);
+        case 4: return launch_decode_s<BF16, LPR, 4, EV>(p, shape, nblk, st);
+        case 2: return launch_decode_s<BF16, LPR, 2, EV>(p, shape, nblk, st);
+        default: return launch_decode_s<BF16, LPR, 1, EV>(p, shape, nblk, st);
     }
 }
 
-hipError_t launch_decode(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
-                         const void* v_new, const float* scale, void* kc, void* vc,
-                         const int64_t* seg_off, const int32_t* caps, int32_t* lens, void* out,
-                         hipStream_t st) {
+template <bool EV>
+static hipError_t launch_decode_any(const pkv_shape& s, const DecodeParams& p, hipStream_t st) {
+    const int G = pick_group(p.grp);
+    const int nblk = s.B * p.nl * (s.H / G);
+    const bool bf16 = s.dtype == PKV_BF16;
+    const int lpr = s.D * (bf16 ? 2 : 4) / 16;
+    const int shape = s.N <= 1024 ? 0 : s.N <= 4096 ? 1 : 2;   // segments hold at most N + appended tokens
+    if (bf16) {
+        if (lpr == 8) return launch_decode_g<true, 8, EV>(p, G, shape, nblk, st);
+        return launch_decode_g<true, 16, EV>(p, G, shape, nblk, st);
+    }
+    if (lpr == 16) return launch_decode_g<false, 16, EV>(p, G, shape, nblk, st);
+    return launch_decode_g<false, 32, EV>(p, G, shape, nblk, st);
+}
+
+static DecodeParams make_params(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
+                                const void* v_new, const float* scale, void* kc, void* vc,
+                                const int64_t* seg_off, const int32_t* caps, int32_t* lens, void* out) {
     DecodeParams p;
     p.B = s.B; p.L = s.L; p.l0 = l0; p.nl = l1 - l0; p.H = s.H; p.Hkv = s.Hkv; p.D = s.D;
     p.grp = s.H / s.Hkv; p.append = k_new != nullptr;
@@ -305,17 +392,25 @@ hipError_t launch_decode(const pkv_shape& s, int l0, int l1, const void* q, cons
     p.v_new = (const unsigned char*)v_new; p.scale = scale;
     p.kc = (unsigned char*)kc; p.vc = (unsigned char*)vc; p.seg_off = seg_off; p.caps = caps;
     p.lens = lens; p.out = (unsigned char*)out;
-    const int G = pick_group(p.grp);
-    const int nblk = s.B * p.nl * (s.H / G);
-    const bool bf16 = s.dtype == PKV_BF16;
-    const int lpr = s.D * (bf16 ? 2 : 4) / 16;
-    const int shape = s.N <= 1024 ? 0 : s.N <= 4096 ? 1 : 2;   // segments hold at most N + appended tokens
-    if (bf16) {
-        if (lpr == 8) return launch_decode_g<true, 8>(p, G, shape, nblk, st);
-        return launch_decode_g<true, 16>(p, G, shape, nblk, st);
-    }
-    if (lpr == 16) return launch_decode_g<false, 16>(p, G, shape, nblk, st);
-    return launch_decode_g<false, 32>(p, G, shape, nblk, st);
+    p.N = s.N; p.t = 0; p.d = 0; p.base_lens = nullptr; p.kept_pos = nullptr;
+    return p;
+}
+
+hipError_t launch_decode(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
+                         const void* v_new, const float* scale, void* kc, void* vc,
+                         const int64_t* seg_off, const int32_t* caps, int32_t* lens, void* out,
+                         hipStream_t st) {
+    const DecodeParams p = make_params(s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, lens, out);
+    return launch_decode_any<false>(s, p, st);
+}
+
+hipError_t launch_decode_evict(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
+                               const void* v_new, const float* scale, void* kc, void* vc,
+                               const int64_t* seg_off, const int32_t* caps, const int32_t* base_lens,
+                               int32_t* lens, int32_t* kept_pos, int t, int d, void* out, hipStream_t st) {
+    DecodeParams p = make_params(s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, lens, out);
+    p.t = t; p.d = d; p.base_lens = base_lens; p.kept_pos = kept_pos;
+    return launch_decode_any<true>(s, p, st);
 }
 
 }  // namespace pkv

@@ -129,6 +129,15 @@ def test_compact_and_decode_argument_errors():
     assert dec(l1=5) == 2
     assert dec(sh=_shape(H=4096, Hkv=2)) == 2
     assert dec(q=C.c_void_p(0x1008)) == 4
+    ev = lambda t=1, d=4, kn=FAKE, base=FAKE, kp=None, sh=s: lib.prefixkv_decode_attn_evict(
+        C.byref(sh), 0, 4, FAKE, kn, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, base, FAKE, kp, t, d, FAKE, None, 0,
+        None)
+    assert ev(kn=None) == 1           # the pruning step always stores a token
+    assert ev(base=None) == 1
+    assert ev(t=0) == 2
+    assert ev(d=0) == 2
+    assert ev(d=65536) == 2
+    assert ev(sh=_shape(D=32)) == 2
 
 
 def test_binding_refuses_cpu_tensors():

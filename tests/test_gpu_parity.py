@@ -342,6 +342,105 @@ def test_decode_matches_oracle(B, L, H, Hkv, N, D, dtype, frac, steps):
     run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed=N + H)
 
 
+# ------------------------------------------------ decode with pruning at a fixed distance (Sec. 3.1)
+def run_evict_case(B, L, H, Hkv, N, D, dtype, frac, d, steps, seed, extra=None, zero_seq=False):
+    g = torch.Generator().manual_seed(seed)
+    k = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+    v = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+    scale = ((torch.rand(L, generator=g) * 2.5 + 0.5) / D ** 0.5).float()
+    imp = synthetic_importance(B, L, N, seed=seed)
+    if zero_seq:
+        imp[0, 0, 0] = float("nan")
+    budget = max(L + 1, int(frac * L * N))
+    sel = oracle.select(imp.numpy(), budget)
+    cap = d + 1 + (steps if extra is None else extra)
+    got, want = run_compact(k, v, sel, cap, budget)
+    base = torch.from_numpy(sel["lengths"]).to(DEV)
+    bf = dtype == torch.bfloat16
+    esz = 2 if bf else 4
+    for t in range(1, steps + 1):
+        q = torch.randn((B, L, H, D), generator=g).to(dtype)
+        kn = torch.randn((B, L, Hkv, D), generator=g).to(dtype)
+        vn = torch.randn((B, L, Hkv, D), generator=g).to(dtype)
+        o = P.prefixkv_decode_attn_evict(got, base, q.to(DEV), kn.to(DEV), vn.to(DEV), scale.to(DEV), N, t, d)
+        ref = oracle.decode_attn_evict(want, sel["lengths"], np32(q), np32(kn), np32(vn), scale.numpy(), N, t, d,
+                                       out_bf16=bf)
+        torch.cuda.synchronize()
+        err = np.abs(np32(o) - ref)
+        assert err.max() <= OUT_ATOL, f"step {t}: max abs err {err.max():.3e}"
+        np.testing.assert_array_equal(got.lens.cpu().numpy(), want["lens"], err_msg=f"step {t}")
+    # every live slot (permanent entries and ring) holds the same position and the same bytes
+    kc, vc, kp = np32(got.kc), np32(got.vc), got.kept_pos.cpu().numpy()
+    nring = min(steps, d + 1)
+    for b in range(B):
+        for l in range(L):
+            off, cp, perm = int(want["seg_off"][b, l]), int(want["caps"][b, l]), int(want["lens"][b, l])
+            slots = list(range(perm)) + list(range(cp - d - 1, cp - d - 1 + nring))
+            wkp = oracle.segment(want, "kept_pos", b, l)
+            np.testing.assert_array_equal(kp[off:off + cp][slots], wkp[slots])
+            live = [s_ for s_ in slots if wkp[s_] >= 0]
+            gk = kc[off * Hkv * D:(off + cp) * Hkv * D].reshape(Hkv, cp, D)
+            gv = vc[off * Hkv * D:(off + cp) * Hkv * D].reshape(Hkv, cp, D)
+            np.testing.assert_array_equal(gk[:, live], oracle.segment(want, "kc", b, l)[:, live])
+            np.testing.assert_array_equal(gv[:, live], oracle.segment(want, "vc", b, l)[:, live])
+    return sel, want
+
+
+@pytest.mark.parametrize("B,L,H,Hkv,N,D,dtype,frac,d,steps", [
+    (1, 4, 2, 2, 128, 64, torch.float32, 0.5, 1, 12),     # the Tiny shape, decide from step 2 on
+    (1, 4, 2, 2, 128, 64, torch.float32, 0.5, 4, 24),
+    (2, 3, 4, 4, 300, 128, torch.bfloat16, 0.3, 3, 30),   # survivors and pruned tokens alternate
+    (2, 2, 8, 2, 500, 128, torch.bfloat16, 0.5, 7, 20),   # GQA group of 4
+    (1, 2, 16, 2, 260, 64, torch.bfloat16, 0.6, 2, 9),    # GQA group of 8, D = 64
+    (1, 2, 6, 2, 150, 128, torch.bfloat16, 0.4, 5, 16),   # group of 3: three workgroups share a kv head
+    (1, 2, 2, 2, 63, 128, torch.bfloat16, 1.0, 2, 8),     # ratio 1: every decided token survives
+    (1, 2, 2, 2, 60, 128, torch.bfloat16, 0.5, 70, 80),   # ring longer than a chunk
+    (1, 2, 4, 4, 1500, 128, torch.bfloat16, 0.7, 6, 10),  # 4-wavefront launch shape
+    (1, 2, 8, 2, 4200, 128, torch.bfloat16, 0.8, 3, 6),   # 8-wavefront launch shape, GQA
+    (1, 3, 2, 2, 64, 64, torch.float32, 0.06, 63, 70),    # one kept entry per layer: sliding window
+])
+def test_decode_evict_matches_oracle(B, L, H, Hkv, N, D, dtype, frac, d, steps):
+    run_evict_case(B, L, H, Hkv, N, D, dtype, frac, d, steps, seed=N + H + d)
+
+
+def test_decode_evict_rejected_sequence_and_size_law():
+    B, L, N, d, steps = 2, 3, 96, 3, 40
+    sel, want = run_evict_case(B, L, 4, 2, N, 128, torch.bfloat16, 0.25, d, steps, seed=5, zero_seq=True)
+    assert sel["lengths"][0].sum() == 0                    # rejected: only the ring is ever cached
+    for b in range(B):
+        for l in range(L):
+            kl = int(sel["lengths"][b, l])
+            target = max(1, (2 * kl * (N + steps) + N) // (2 * N))
+            assert int(want["lens"][b, l]) + d == max(target, kl + d)
+
+
+def test_decode_evict_without_position_tracking_and_capacity_guard():
+    """kept_pos = NULL is allowed; a segment whose capacity cannot hold the ring is left alone and
+    outputs zeros (device-side guard; the oracle refuses such a call, so there is no reference)."""
+    B, L, H, Hkv, N, D, d = 1, 2, 2, 2, 50, 64, 4
+    g = torch.Generator().manual_seed(3)
+    k = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    v = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    sel = oracle.select(synthetic_importance(B, L, N, seed=8).numpy(), 40)
+    scale = torch.full((L,), 0.1)
+    q = torch.randn((B, L, H, D), generator=g).to(torch.bfloat16)
+    kn = torch.randn((B, L, Hkv, D), generator=g).to(torch.bfloat16)
+    base = torch.from_numpy(sel["lengths"]).to(DEV)
+    got, want = run_compact(k, v, sel, d + 1, 40)
+    before = got.kept_pos.clone()
+    o = P.prefixkv_decode_attn_evict(got, base, q.to(DEV), kn.to(DEV), kn.to(DEV), scale.to(DEV), N, 1, d,
+                                     track_positions=False)
+    ref = oracle.decode_attn_evict(want, sel["lengths"], np32(q), np32(kn), np32(kn), scale.numpy(), N, 1, d,
+                                   out_bf16=True)
+    assert np.abs(np32(o) - ref).max() <= OUT_ATOL
+    assert torch.equal(before, got.kept_pos)
+    small, _ = run_compact(k, v, sel, d, 40)               # one slot short of a ring
+    kc0, lens0 = small.kc.clone(), small.lens.clone()
+    o = P.prefixkv_decode_attn_evict(small, base, q.to(DEV), kn.to(DEV), kn.to(DEV), scale.to(DEV), N, 1, d)
+    torch.cuda.synchronize()
+    assert (o == 0).all() and torch.equal(kc0, small.kc) and torch.equal(lens0, small.lens)
+
+
 def test_decode_layer_range_and_rejected_sequence():
     run_decode_case(2, 4, 4, 4, 100, 128, torch.bfloat16, 0.3, 2, seed=7, layer_range=(1, 3))
     run_decode_case(2, 3, 4, 2, 100, 128, torch.bfloat16, 0.3, 2, seed=8, zero_seq=True)
