@@ -26,11 +26,21 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 
-def algorithmic_decode_bytes(lens0_sum: int, n_seg: int, t: int, H: int, Hkv: int, D: int, esz: int) -> int:
+def algorithmic_decode_bytes(lens0_sum: int, n_seg: int, t: int, H: int, Hkv: int, D: int, esz: int,
+                             tokens: int = None) -> int:
     """HBM bytes the method itself must move in decode step t (0-based): every occupied slot of K and V
     once (including the token appended in this step), q in, out out, and the appended k/v written."""
-    tokens = lens0_sum + n_seg * (t + 1)
+    if tokens is None:
+        tokens = lens0_sum + n_seg * (t + 1)
     return tokens * Hkv * D * esz * 2 + n_seg * (2 * H + 2 * Hkv) * D * esz
+
+
+def cached_tokens_under_pruning(lens0, N: int, t: int, d: int) -> int:
+    """Entries cached after 1-based step t when decoding with pruning at distance d, summed over all
+    segments: max(target(t), k + min(t, d)) with target = round-half-up(k (N+t) / N), at least 1."""
+    k = lens0.to("cpu").long()
+    target = ((2 * k * (N + t) + N) // (2 * N)).clamp(min=1)
+    return int(torch.maximum(target, k + min(t, d)).sum())
 
 
 def main() -> int:
@@ -41,6 +51,8 @@ def main() -> int:
     ap.add_argument("--config", default="llava7b_b1")
     ap.add_argument("--budget", type=float, default=None)
     ap.add_argument("--decode-steps", type=int, default=None)
+    ap.add_argument("--evict-distance", type=int, default=None, metavar="D",
+                    help="decode with pruning at distance D from the newest token instead of append-only")
     ap.add_argument("--no-graph", action="store_true", help="launch every decode step from Python")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
@@ -79,7 +91,7 @@ def main() -> int:
 
     x = make_prefill(w, device=dev)
     dec = make_decode(w, device=dev)
-    hp = HotPath(x["q"], x["k"], x["v"], x["scale"], Bk, T)
+    hp = HotPath(x["q"], x["k"], x["v"], x["scale"], Bk, T, evict_distance=args.evict_distance)
     dq, dk, dv = dec["q"], dec["k"], dec["v"]
     use_graph = not args.no_graph
 
@@ -119,7 +131,14 @@ def main() -> int:
     stage_ms = [sum(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(K)) / K for j in range(4)]
     imp_ms, sel_ms, cmp_ms, dec_ms = stage_ms
     tok_s = w.B * T / (dec_ms * 1e-3)
-    assert int(hp.cache.lens.sum()) == int(lens0.sum()) + w.B * w.L * T, "decode loop did not run to the end"
+    d_ev = args.evict_distance
+    if d_ev is None:
+        assert int(hp.cache.lens.sum()) == int(lens0.sum()) + w.B * w.L * T, "decode loop did not run to the end"
+        step_tokens = [None] * T
+    else:
+        assert int(hp.cache.lens.sum()) + w.B * w.L * min(T, d_ev) == cached_tokens_under_pruning(lens0, w.N, T, d_ev), \
+            "decode loop did not run to the end"
+        step_tokens = [cached_tokens_under_pruning(lens0, w.N, t + 1, d_ev) for t in range(T)]
 
     # ---- roofline of the dominant kernel (decode_attn_kernel).  The decode loop is T launches of that
     # one kernel and nothing else, back to back on one stream (a HIP graph by default), so the event
@@ -127,18 +146,22 @@ def main() -> int:
     n_seg, esz = w.B * w.L, w.elem_bytes
     kern_ms = dec_ms / T
     lens0_sum = int(lens0.sum())
-    alg_bytes = sum(algorithmic_decode_bytes(lens0_sum, n_seg, t, w.H, w.Hkv, w.D, esz) for t in range(T)) / T
+    alg_bytes = sum(algorithmic_decode_bytes(lens0_sum, n_seg, t, w.H, w.Hkv, w.D, esz, step_tokens[t])
+                    for t in range(T)) / T
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"decode_attn_kernel/{w.name}/budget{r:g}")
+        key = f"decode_attn_kernel/{w.name}/budget{r:g}" + ("" if d_ev is None else f"/evict{d_ev}")
+        traffic = json.load(open(tpath)).get(key)
     roofline = {"kernel": "decode_attn_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "bytes_per_launch": int(alg_bytes), "kernel_ms": round(kern_ms, 5),
                 "launches_per_step": T,
-                "first_launch_bytes": algorithmic_decode_bytes(lens0_sum, n_seg, 0, w.H, w.Hkv, w.D, esz),
-                "last_launch_bytes": algorithmic_decode_bytes(lens0_sum, n_seg, T - 1, w.H, w.Hkv, w.D, esz)}
+                "first_launch_bytes": algorithmic_decode_bytes(lens0_sum, n_seg, 0, w.H, w.Hkv, w.D, esz,
+                                                               step_tokens[0]),
+                "last_launch_bytes": algorithmic_decode_bytes(lens0_sum, n_seg, T - 1, w.H, w.Hkv, w.D, esz,
+                                                              step_tokens[T - 1])}
     flops = 2 * w.B * w.L * w.H * w.N * (w.N + 1) * w.D   # two causal QK^T passes (lse, column sums)
     imp_tflops = flops / (imp_ms * 1e-3) / 1e12
     cmp_bytes = 2 * lens0_sum * w.Hkv * w.D * esz * 2 + w.B * w.L * w.N * 4
@@ -162,7 +185,8 @@ def main() -> int:
         "ms_per_step": round(wall * 1e3 / K, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "L": w.L, "H": w.H, "Hkv": w.Hkv, "D": w.D, "N": w.N,
-                   "budget": r, "budget_tokens": Bk, "decode_steps": T},
+                   "budget": r, "budget_tokens": Bk, "decode_steps": T,
+                   "decode_mode": "append" if d_ev is None else f"prune at distance {d_ev}"},
         "prefixkv_select_ms": round(sel_ms, 4),
         "stages": extra, "roofline": roofline, "cpu_baseline": cpu,
     }

@@ -13,12 +13,16 @@ from . import binding as B_
 class HotPath:
     def __init__(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: torch.Tensor,
                  budget_tokens: int, decode_steps: int, tol_tokens: int = 0, max_iters: int = 64,
-                 fixup: bool = True):
+                 fixup: bool = True, evict_distance: Optional[int] = None):
         self.q, self.k, self.v, self.scale = q, k, v, scale
         self.B, self.L, self.H, self.N, self.D = q.shape
         self.Hkv = k.shape[2]
         self.budget_tokens, self.T = int(budget_tokens), int(decode_steps)
         self.tol_tokens, self.max_iters, self.fixup = tol_tokens, max_iters, fixup
+        # append-only decode needs one slot per step; pruning at a fixed distance needs the ring plus
+        # room for the survivors (never more than one per step)
+        self.evict_distance = evict_distance
+        self.decode_capacity = self.T if evict_distance is None else evict_distance + 1 + self.T
         dev, dt = q.device, q.dtype
         Bn, L, H, N, D, Hkv = self.B, self.L, self.H, self.N, self.D, self.Hkv
         code = B_.PKV_F32 if dt == torch.float32 else B_.PKV_BF16
@@ -36,7 +40,7 @@ class HotPath:
             status=torch.empty(Bn, dtype=torch.int32, device=dev))
         self.sel_ws = torch.empty(max(256, Bn * L * 4), dtype=torch.uint8, device=dev)
         budget_cap = min(self.budget_tokens, L * N)
-        self.cache_tokens = B_.prefixkv_cache_tokens_upper_bound(Bn, budget_cap, L, self.T)
+        self.cache_tokens = B_.prefixkv_cache_tokens_upper_bound(Bn, budget_cap, L, self.decode_capacity)
         self.cache = B_.CompactResult(
             kc=torch.empty(self.cache_tokens * Hkv * D, dtype=dt, device=dev),
             vc=torch.empty(self.cache_tokens * Hkv * D, dtype=dt, device=dev),
@@ -57,10 +61,13 @@ class HotPath:
                                   self.fixup, out=self.sel, ws=self.sel_ws)
 
     def run_compact(self):
-        return B_.prefixkv_compact(self.k, self.v, self.sel.order, self.sel.lengths, self.T,
+        return B_.prefixkv_compact(self.k, self.v, self.sel.order, self.sel.lengths, self.decode_capacity,
                                    self.cache_tokens, out=self.cache)
 
     def run_decode_step(self, t: int, dq, dk, dv):
+        if self.evict_distance is not None:
+            return B_.prefixkv_decode_attn_evict(self.cache, self.sel.lengths, dq[t], dk[t], dv[t], self.scale,
+                                                 self.N, t + 1, self.evict_distance, out=self.out[t])
         return B_.prefixkv_decode_attn(self.cache, dq[t], dk[t], dv[t], self.scale, self.N, out=self.out[t])
 
     def run_decode_loop(self, dq, dk, dv):

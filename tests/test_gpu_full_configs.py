@@ -134,3 +134,59 @@ def test_llava13b_b8_sampled_sequence():
 @pytest.mark.timeout(400)
 def test_gqa_long_sampled_sequence_and_tail_columns():
     run_config("gqa_long", 0.1, sample_b=2, steps=2, imp_layers=[0, 19], imp_tail=160)
+
+
+def run_config_pruning(name, budget, sample_b, steps, d):
+    """The same pipeline with the decode loop pruning at distance d (one HIP graph of `steps` launches);
+    the sampled sequence is checked against the oracle step by step, the whole batch against the closed
+    form of the cache size."""
+    w = CONFIGS[name]
+    Bk = w.budget_tokens(budget)
+    x = make_prefill(w, device=DEV)
+    dec = make_decode(w, steps=steps, device=DEV)
+    hp = HotPath(x["q"], x["k"], x["v"], x["scale"], Bk, steps, evict_distance=d)
+    hp.run_importance(); hp.run_select(); hp.run_compact()
+    torch.cuda.synchronize()
+    scale = x["scale"].cpu().numpy()
+    lengths = hp.sel.lengths.cpu().numpy()
+    b = sample_b
+    want = oracle.select(hp.importance[b:b + 1].cpu().numpy(), Bk)
+    np.testing.assert_array_equal(lengths[b:b + 1], want["lengths"])
+    ocache = oracle.compact(f32(x["k"][b:b + 1]), f32(x["v"][b:b + 1]), want["order"], want["lengths"],
+                            hp.decode_capacity)
+    dq, dk, dv = dec["q"], dec["k"], dec["v"]
+    hp.capture_decode_loop(dq, dk, dv)
+    hp.run_compact()
+    hp.replay_decode_loop()
+    torch.cuda.synchronize()
+    bf = w.dtype == "bf16"
+    for t in range(steps):
+        ref = oracle.decode_attn_evict(ocache, want["lengths"], f32(dq[t, b:b + 1]), f32(dk[t, b:b + 1]),
+                                       f32(dv[t, b:b + 1]), scale, w.N, t + 1, d, out_bf16=bf)
+        err = np.abs(f32(hp.out[t, b:b + 1]) - ref).max()
+        assert err <= OUT_ATOL, f"decode step {t + 1}: max abs err {err:.3e}"
+    perm = hp.cache.lens.cpu().numpy()
+    np.testing.assert_array_equal(perm[b:b + 1], ocache["lens"])
+    k64 = lengths.astype(np.int64)
+    target = np.maximum(1, (2 * k64 * (w.N + steps) + w.N) // (2 * w.N))
+    np.testing.assert_array_equal(perm + min(steps, d), np.maximum(target, k64 + min(steps, d)))
+    # labels of the sampled sequence's slots: permanent entries and ring
+    seg_off, caps = hp.cache.seg_off.cpu().numpy(), hp.cache.caps.cpu().numpy()
+    kp = hp.cache.kept_pos.cpu().numpy()
+    for l in range(w.L):
+        off, cp, pm = int(seg_off[b, l]), int(caps[b, l]), int(perm[b, l])
+        slots = list(range(pm)) + list(range(cp - d - 1, cp - d - 1 + min(steps, d + 1)))
+        np.testing.assert_array_equal(kp[off:off + cp][slots], oracle.segment(ocache, "kept_pos", 0, l)[slots])
+    assert torch.isfinite(hp.out.float()).all()
+
+
+def test_tiny_pruning_decode():
+    run_config_pruning("tiny", 0.5, 0, steps=24, d=4)
+
+
+def test_llava7b_b1_pruning_decode():
+    run_config_pruning("llava7b_b1", 0.2, 0, steps=40, d=8)
+
+
+def test_llava7b_b16_pruning_decode_sampled_sequence():
+    run_config_pruning("llava7b_b16", 0.2, sample_b=7, steps=12, d=5)
