@@ -51,6 +51,7 @@ def main() -> int:
     ap.add_argument("--config", default="llava7b_b1")
     ap.add_argument("--budget", type=float, default=None)
     ap.add_argument("--decode-steps", type=int, default=None)
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size of the workload")
     ap.add_argument("--evict-distance", type=int, default=None, metavar="D",
                     help="decode with pruning at distance D from the newest token instead of append-only")
     ap.add_argument("--no-graph", action="store_true", help="launch every decode step from Python")
@@ -83,6 +84,8 @@ def main() -> int:
     w = CONFIGS[args.config]
     if args.decode_steps is not None:
         w = w.with_(decode_steps=args.decode_steps)
+    if args.batch is not None:
+        w = w.with_(B=args.batch)
     r = w.budget if args.budget is None else args.budget
     Bk = w.budget_tokens(r)
     dev = "cuda:0"

@@ -336,10 +336,24 @@ static int pick_group(int grp) { return grp % 8 == 0 ? 8 : grp % 4 == 0 ? 4 : gr
 // Launch shapes.  All workgroups of a launch should be resident at once (one round), so short
 // segments get small workgroups with many row loads in flight per wavefront, and long segments get
 // more wavefronts per workgroup to shorten the serial walk over the chunks:
-//   shape 0: 2 wavefronts, 16 loads in flight, 2 wavefronts/SIMD   (segments up to ~1k tokens)
+//   shape 0: 2 wavefronts, 16 loads in flight, 2 wavefronts/SIMD   (segments up to ~1k tokens);
+//            with more than one resident round of workgroups: 4 loads in flight, 4 wavefronts/SIMD
 //   shape 1: 4 wavefronts,  8 loads in flight, 4 wavefronts/SIMD   (up to ~4k tokens)
 //   shape 2: 8 wavefronts,  8 loads in flight, 4 wavefronts/SIMD   (longer)
 // Groups of 4 or 8 query heads keep 8 loads in flight and 2 wavefronts/SIMD (register budget).
+// Number of compute units of the current device (queried once per device).
+static int compute_units() {
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 template <bool BF16, int LPR, int G, bool EV>
 static hipError_t launch_decode_s(const DecodeParams& p, int shape, int nblk, hipStream_t st) {
     constexpr int RPI = kWave / LPR;
@@ -348,6 +362,15 @@ static hipError_t launch_decode_s(const DecodeParams& p, int shape, int nblk, hi
     constexpr int NI16 = WIDE ? (NI_MAX < 8 ? NI_MAX : 8) : (NI_MAX < 16 ? NI_MAX : 16);
     constexpr int NI8 = NI_MAX < 8 ? NI_MAX : 8;
     constexpr int OCC4 = WIDE ? 2 : 4;
+    if constexpr (!WIDE) {
+        // more workgroups than fit on the chip at once: smaller register footprint, twice as many resident
+        // workgroups with a quarter of the loads in flight each (measured 4-27 % faster from batch 2 on)
+        constexpr int NI4 = NI_MAX < 4 ? NI_MAX : 4;
+        if (shape == 0 && nblk > 4 * compute_units()) {
+            hipLaunchKernelGGL((decode_attn_kernel<BF16, LPR, G, NI4, 2, 4, EV>), dim3(nblk), dim3(2 * kWave), 0, st, p);
+            return hipGetLastError();
+        }
+    }
     if (shape == 0)
         hipLaunchKernelGGL((decode_attn_kernel<BF16, LPR, G, NI16, 2, 2, EV>), dim3(nblk), dim3(2 * kWave), 0, st, p);
     else if (shape == 1)
