@@ -329,6 +329,268 @@ decode_attn_kernel(DecodeParams p) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Grouped-query variant on the matrix cores (bf16 storage, G = 2, 4 or 8 query heads per KV head).
+// With several query heads per cached row the dot products dominate the vector ALU, so they move to
+// MFMA: scores^T[16 rows x 16 head columns] = K[16 rows x D] . Q^T[D x heads] with
+// v_mfma_f32_16x16x32_bf16 (A = cache rows, one row per lane%16, 8 consecutive bf16 per lane; B = the
+// queries, head lane%16, columns >= G are zero).  A lane then holds the scores of one head for 4 rows;
+// softmax runs in that layout (one exp per (row, head) instead of one per lane of the row), the
+// probabilities go through a per-wavefront LDS tile to the layout of the V rows (LPR lanes per row, as in
+// the kernel above), and the weighted V sum stays on the vector ALU with fp32 accumulators.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int D, int G, int NT, int W, int OCC, bool EV>
+__global__ void __launch_bounds__(W * kWave, OCC)
+decode_gqa_kernel(DecodeParams p) {
+    constexpr int LPR = D / 8;                   // lanes per V row (16 bytes each)
+    constexpr int RPI = kWave / LPR;             // V rows per wavefront-wide load
+    constexpr int NJ = D / 32;                   // MFMAs per 16-row tile
+    constexpr int BR = NT * 16;                  // rows per block
+    constexpr int VI = BR / RPI;                 // V loads per block
+    constexpr int GP = G < 4 ? 4 : G;            // head columns kept in LDS
+    constexpr int DMAX = 128;
+    constexpr int ROWB = D * 2;
+    static_assert(D == 64 || D == 128, "head dimension");
+    __shared__ float s_part[W][G][DMAX + 2];
+    __shared__ __attribute__((aligned(16))) float s_p[W][BR * GP];
+    __shared__ __attribute__((aligned(16))) float s_corr[W][GP];
+
+    const int HU = p.H / G;
+    const int hu = blockIdx.x % HU, i_seg = blockIdx.x / HU;
+    const int b = i_seg / p.nl, l = p.l0 + i_seg % p.nl, sl = b * p.L + l;
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    const int sub = lane % LPR, rg = lane / LPR;     // V layout
+    const int kr = lane & 15, kq = lane >> 4;        // K / score layout: row (or head) kr, quad kq
+
+    const int len_old = __hip_atomic_load(p.lens + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kLenMask;
+    const int cap = p.caps[sl];
+    const int64_t off = p.seg_off[sl];
+    bool app = p.append && len_old < cap;
+    int len = len_old + (app ? 1 : 0), len_next = len;
+    RingMap ring = {0, app ? len_old : -1, -1};
+    int ring0 = 0, cs = 0;
+    bool grad = false, decide = false;
+    if constexpr (EV) {
+        const int base = p.base_lens[sl];
+        ring0 = cap - (p.d + 1);
+        app = base >= 0 && ring0 >= base && len_old <= ring0;
+        decide = app && p.t > p.d;
+        cs = p.t % (p.d + 1);
+        long long target = (2ll * base * ((long long)p.N + p.t) + p.N) / (2ll * p.N);
+        target = target < 1 ? 1 : target;
+        grad = decide && (long long)len_old + p.d + 1 <= target && len_old < ring0;
+        ring.shift = ring0 - len_old;
+        ring.r_new = app ? len_old + (p.t - 1) % (p.d + 1) : -1;
+        ring.r_mask = (decide && !grad) ? len_old + cs : -1;
+        len = app ? len_old + (p.t < p.d + 1 ? p.t : p.d + 1) : 0;
+        len_next = len_old + (grad ? 1 : 0);
+    }
+    const int nblk = (len + BR - 1) / BR;
+    const int kvh = (hu * G) / p.grp;
+    const bool writer = app && ((hu * G) % p.grp == 0);
+    const int64_t segbase = (off * p.Hkv + (int64_t)kvh * cap) * ROWB;
+    const unsigned char* knew = p.k_new + ((int64_t)sl * p.Hkv + kvh) * ROWB;
+    const unsigned char* vnew = p.v_new + ((int64_t)sl * p.Hkv + kvh) * ROWB;
+    unsigned char* kseg = p.kc + segbase;
+    unsigned char* vseg = p.vc + segbase;
+
+    float o[G][8], m_run = -INFINITY, l_run = 0.f;
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int x = 0; x < 8; ++x) o[g][x] = 0.f;
+
+    if (wv < nblk) {
+        const float qs = p.scale[l] * 1.4426950408889634f;
+        bf16x8_t qb[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            uint4 t = make_uint4(0, 0, 0, 0);
+            if (kr < G) t = *(const uint4*)(p.q + ((int64_t)sl * p.H + hu * G + kr) * ROWB + (4 * j + kq) * 16);
+            qb[j] = __builtin_bit_cast(bf16x8_t, t);
+        }
+        float* ps = s_p[wv];
+        float* cr = s_corr[wv];
+        for (int blk = wv; blk < nblk; blk += W) {
+            const int r0 = blk * BR;
+            const bool full = r0 + BR <= len_old;
+            if constexpr (EV) {
+                const int hi = len < r0 + BR ? len : r0 + BR;
+                if (hi - r0 == 1 && ring.r_mask == r0) continue;
+            }
+            uint4 kf[NT][NJ], vr[VI];
+            if (full) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        kf[t][j] = load_stream16(kseg + (uint32_t)(r0 + 16 * t + kr) * ROWB + (4 * j + kq) * 16);
+#pragma unroll
+                for (int i = 0; i < VI; ++i)
+                    vr[i] = load_stream16(vseg + (uint32_t)(r0 + i * RPI + rg) * ROWB + sub * 16);
+            } else {
+                // guarded path: rows past the end are zero, the new row comes from k_new / v_new and is stored,
+                // under pruning ring rows map to the ring slots and the pruned row is left out
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int r = r0 + 16 * t + kr;
+                    const bool valid = r < len && r != ring.r_mask;
+                    const bool isnew = r == ring.r_new;
+                    const uint32_t so = (uint32_t)(r + ((EV && r >= len_old) ? ring.shift : 0)) * ROWB;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        const int c16 = (4 * j + kq) * 16;
+                        kf[t][j] = make_uint4(0, 0, 0, 0);
+                        if (valid) {
+                            kf[t][j] = load_stream16(isnew ? knew + c16 : kseg + so + c16);
+                            if (isnew && writer) *(uint4*)(kseg + so + c16) = kf[t][j];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < VI; ++i) {
+                    const int r = r0 + i * RPI + rg;
+                    const bool valid = r < len && r != ring.r_mask;
+                    const bool isnew = r == ring.r_new;
+                    const uint32_t so = (uint32_t)(r + ((EV && r >= len_old) ? ring.shift : 0)) * ROWB;
+                    vr[i] = make_uint4(0, 0, 0, 0);
+                    if (valid) {
+                        vr[i] = load_stream16(isnew ? vnew + sub * 16 : vseg + so + sub * 16);
+                        if (isnew && writer) *(uint4*)(vseg + so + sub * 16) = vr[i];
+                    }
+                }
+            }
+            // scores: one MFMA chain per 16-row tile
+            f32x4_t acc[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                acc[t] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[t][j]), qb[j],
+                                                                     acc[t], 0, 0, 0);
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float sc = acc[t][r] * qs;
+                    if (!full) {
+                        const int row = r0 + 16 * t + 4 * kq + r;
+                        sc = (row < len && row != ring.r_mask) ? sc : -INFINITY;
+                    }
+                    acc[t][r] = sc;
+                    mx = fmaxf(mx, sc);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            const float mnew = fmaxf(m_run, mx);              // finite: the block has an occupied row
+            const float corr = __builtin_amdgcn_exp2f(m_run - mnew);
+            m_run = mnew;
+            float psum = 0.f;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float pr = __builtin_amdgcn_exp2f(acc[t][r] - mnew);
+                    psum += pr;
+                    if (kr < GP) ps[(16 * t + 4 * kq + r) * GP + kr] = pr;
+                }
+            l_run = l_run * corr + psum;
+            if (kq == 0 && kr < GP) cr[kr] = corr;
+            wave_lds_sync();
+            float cg[GP];
+#pragma unroll
+            for (int g4 = 0; g4 < GP; g4 += 4) {
+                const float4 c4 = *(const float4*)(cr + g4);
+                cg[g4] = c4.x; cg[g4 + 1] = c4.y; cg[g4 + 2] = c4.z; cg[g4 + 3] = c4.w;
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int x = 0; x < 8; ++x) o[g][x] *= cg[g];
+#pragma unroll
+            for (int i = 0; i < VI; ++i) {
+                float vf[8], pg[GP];
+                unpack16<true>(vr[i], vf);
+#pragma unroll
+                for (int g4 = 0; g4 < GP; g4 += 4) {
+                    const float4 p4 = *(const float4*)(ps + (i * RPI + rg) * GP + g4);
+                    pg[g4] = p4.x; pg[g4 + 1] = p4.y; pg[g4 + 2] = p4.z; pg[g4 + 3] = p4.w;
+                }
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) o[g][x] = fmaf(pg[g], vf[x], o[g][x]);
+            }
+            wave_lds_sync();
+        }
+        // the four quads hold partial row sums of the same head; the RPI row groups partial outputs
+        l_run += __shfl_xor(l_run, 16, kWave);
+        l_run += __shfl_xor(l_run, 32, kWave);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int sh = LPR; sh < kWave; sh <<= 1)
+#pragma unroll
+                for (int x = 0; x < 8; ++x) o[g][x] += __shfl_xor(o[g][x], sh, kWave);
+    }
+    if constexpr (EV) {
+        if (grad && writer && wv == 0 && rg == 0) {
+            const size_t src = (size_t)(ring0 + cs) * ROWB + sub * 16, dst = (size_t)len_old * ROWB + sub * 16;
+            *(uint4*)(kseg + dst) = *(const uint4*)(kseg + src);
+            *(uint4*)(vseg + dst) = *(const uint4*)(vseg + src);
+        }
+        if (p.kept_pos && app && hu == 0 && threadIdx.x == 0) {
+            int32_t* kp = p.kept_pos + off;
+            kp[ring0 + (p.t - 1) % (p.d + 1)] = p.N + p.t - 1;
+            if (decide) {
+                if (grad) kp[len_old] = p.N + p.t - p.d - 1;
+                kp[ring0 + cs] = -1;
+            }
+        }
+    }
+    if (rg == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int x = 0; x < 8; ++x) s_part[wv][g][sub * 8 + x] = o[g][x];
+    }
+    if (kq == 0 && kr < G) { s_part[wv][kr][DMAX] = m_run; s_part[wv][kr][DMAX + 1] = l_run; }
+    __syncthreads();
+    for (int i = threadIdx.x; i < G * D; i += blockDim.x) {
+        const int g = i / D, d = i % D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < W; ++w) M = fmaxf(M, s_part[w][g][DMAX]);
+        float num = 0.f, den = 0.f;
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+                const float wgt = __builtin_amdgcn_exp2f(s_part[w][g][DMAX] - M);
+                num = fmaf(wgt, s_part[w][g][d], num);
+                den = fmaf(wgt, s_part[w][g][DMAX + 1], den);
+            }
+        }
+        const float r = den > 0.f ? num / den : 0.f;
+        ((bf16_t*)p.out)[((size_t)sl * p.H + hu * G + g) * D + d] = f32_to_bf16(r);
+    }
+    if (threadIdx.x == 0) {
+        const int old = atomicAdd(p.lens + sl, 1 << kLenBits);
+        if ((int)((unsigned)old >> kLenBits) == HU - 1)
+            __hip_atomic_store(p.lens + sl, len_next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 size_t decode_ws_bytes(const pkv_shape&) { return 0; }
 
 static int pick_group(int grp) { return grp % 8 == 0 ? 8 : grp % 4 == 0 ? 4 : grp % 2 == 0 ? 2 : 1; }
@@ -390,11 +652,36 @@ static hipError_t launch_decode_g(const DecodeParams& p, int G, int shape, int n
     }
 }
 
+// Grouped-query bf16 launches: W wavefronts per workgroup by segment length, 64-row blocks.
+template <int D, int G, bool EV>
+static hipError_t launch_gqa_s(const DecodeParams& p, int shape, int nblk, hipStream_t st) {
+    if (shape == 0)
+        hipLaunchKernelGGL((decode_gqa_kernel<D, G, 4, 2, 2, EV>), dim3(nblk), dim3(2 * kWave), 0, st, p);
+    else if (shape == 1)
+        hipLaunchKernelGGL((decode_gqa_kernel<D, G, 4, 4, 2, EV>), dim3(nblk), dim3(4 * kWave), 0, st, p);
+    else
+        hipLaunchKernelGGL((decode_gqa_kernel<D, G, 4, 8, 2, EV>), dim3(nblk), dim3(8 * kWave), 0, st, p);
+    return hipGetLastError();
+}
+
+template <int D, bool EV>
+static hipError_t launch_gqa(const DecodeParams& p, int G, int shape, int nblk, hipStream_t st) {
+    switch (G) {
+        case 8: return launch_gqa_s<D, 8, EV>(p, shape, nblk, st);
+        case 4: return launch_gqa_s<D, 4, EV>(p, shape, nblk, st);
+        default: return launch_gqa_s<D, 2, EV>(p, shape, nblk, st);
+    }
+}
+
 template <bool EV>
 static hipError_t launch_decode_any(const pkv_shape& s, const DecodeParams& p, hipStream_t st) {
     const int G = pick_group(p.grp);
     const int nblk = s.B * p.nl * (s.H / G);
     const bool bf16 = s.dtype == PKV_BF16;
+    if (bf16 && G >= 2) {   // several query heads share the cached rows: scores on the matrix cores
+        const int shp = s.N <= 1024 ? 0 : s.N <= 4096 ? 1 : 2;
+        return s.D == 128 ? launch_gqa<128, EV>(p, G, shp, nblk, st) : launch_gqa<64, EV>(p, G, shp, nblk, st);
+    }
     const int lpr = s.D * (bf16 ? 2 : 4) / 16;
     const int shape = s.N <= 1024 ? 0 : s.N <= 4096 ? 1 : 2;   // segments hold at most N + appended tokens
     if (bf16) {
