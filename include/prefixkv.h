@@ -175,7 +175,11 @@ int64_t prefixkv_cache_tokens_upper_bound(int B, int64_t budget_tokens, int L, i
  *   kc, vc, seg_off, caps as produced by prefixkv_compact
  *   lens [dev] in/out: plain lengths below 2^20 before and after the call.  WHILE the launch runs
  *       the library keeps a completion count in the bits above 2^20 of each entry, so lens must
- *       not be read or written by anything else until the launch has finished.  H <= 2048. */
+ *       not be read or written by anything else until the launch has finished.  H <= 2048.
+ *   ws: needed when several query heads share a KV head and the cache is bf16 (the segments are cut into
+ *       pieces of similar size and the pieces' partial results meet in the workspace);
+ *       prefixkv_workspace_bytes(PKV_OP_DECODE, shape, 0) gives the size (0 when none is needed, then
+ *       ws may be NULL).  The size is for layer range [0,L); a smaller workspace is PKV_ERR_WORKSPACE. */
 int prefixkv_decode_attn(const pkv_shape *shape, int l0, int l1, const void *q, const void *k_new,
                          const void *v_new, const float *scale, void *kc, void *vc,
                          const int64_t *seg_off, const int32_t *caps, int32_t *lens, void *out,

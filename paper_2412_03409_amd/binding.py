@@ -312,7 +312,7 @@ def prefixkv_compact(k: torch.Tensor, v: torch.Tensor, order: torch.Tensor, leng
 def prefixkv_decode_attn(cache: CompactResult, q: torch.Tensor, k_new: Optional[torch.Tensor],
                          v_new: Optional[torch.Tensor], scale: torch.Tensor, N: int,
                          l0: int = 0, l1: Optional[int] = None,
-                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                         out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
     """One decode step over layers [l0,l1): q [B,L,H,D], k_new/v_new [B,L,Hkv,D] or None
     -> out [B,L,H,D].  Appends in place and advances cache.lens on the device."""
     _need_cuda(q, k_new, v_new, scale, out)
@@ -328,9 +328,11 @@ def prefixkv_decode_attn(cache: CompactResult, q: torch.Tensor, k_new: Optional[
     if out is None:
         out = torch.empty((B, L, H, D), dtype=q.dtype, device=q.device)
     s = _shape(B, L, H, cache.Hkv, N, D, _dtype_code(q))
+    w = _ws(load().prefixkv_workspace_bytes(OP_DECODE, C.byref(s), 0), q.device, ws)
     rc = load().prefixkv_decode_attn(C.byref(s), int(l0), int(l1), _ptr(q), _ptr(k_new), _ptr(v_new),
                                      _ptr(scale), _ptr(cache.kc), _ptr(cache.vc), _ptr(cache.seg_off),
-                                     _ptr(cache.caps), _ptr(cache.lens), _ptr(out), None, 0, _stream())
+                                     _ptr(cache.caps), _ptr(cache.lens), _ptr(out), _ptr(w),
+                                     w.numel() * w.element_size(), _stream())
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_decode_attn")
     return out
@@ -339,7 +341,8 @@ def prefixkv_decode_attn(cache: CompactResult, q: torch.Tensor, k_new: Optional[
 def prefixkv_decode_attn_evict(cache: CompactResult, base_lens: torch.Tensor, q: torch.Tensor,
                                k_new: torch.Tensor, v_new: torch.Tensor, scale: torch.Tensor, N: int, t: int,
                                distance: int, l0: int = 0, l1: Optional[int] = None,
-                               track_positions: bool = True, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                               track_positions: bool = True, out: Optional[torch.Tensor] = None,
+                               ws: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Decode step t (1-based) with pruning at `distance` from the newest token; cache.lens counts the
     permanent entries.  base_lens [B,L] i32 = the lengths the cache was compacted with."""
     _need_cuda(q, k_new, v_new, scale, base_lens, out)
@@ -357,10 +360,12 @@ def prefixkv_decode_attn_evict(cache: CompactResult, base_lens: torch.Tensor, q:
     if out is None:
         out = torch.empty((B, L, H, D), dtype=q.dtype, device=q.device)
     s = _shape(B, L, H, cache.Hkv, N, D, _dtype_code(q))
+    w = _ws(load().prefixkv_workspace_bytes(OP_DECODE, C.byref(s), 0), q.device, ws)
     rc = load().prefixkv_decode_attn_evict(
         C.byref(s), int(l0), int(l1), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(scale), _ptr(cache.kc),
         _ptr(cache.vc), _ptr(cache.seg_off), _ptr(cache.caps), _ptr(base_lens), _ptr(cache.lens),
-        _ptr(cache.kept_pos) if track_positions else None, int(t), int(distance), _ptr(out), None, 0, _stream())
+        _ptr(cache.kept_pos) if track_positions else None, int(t), int(distance), _ptr(out), _ptr(w),
+        w.numel() * w.element_size(), _stream())
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_decode_attn_evict")
     return out

@@ -142,8 +142,9 @@ int prefixkv_decode_attn(const pkv_shape* s, int l0, int l1, const void* q, cons
     if (!aligned16(q) || !aligned16(kc) || !aligned16(vc) || !aligned16(out) || !aligned16(k_new) ||
         !aligned16(v_new))
         return PKV_ERR_STRIDE;
-    (void)ws; (void)ws_bytes;  // this stage needs no scratch
-    const hipError_t e = launch_decode(*s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, lens, out,
+    const size_t need = decode_ws_bytes(*s);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return PKV_ERR_WORKSPACE;
+    const hipError_t e = launch_decode(*s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, lens, out, ws,
                                        (hipStream_t)stream);
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
@@ -161,9 +162,10 @@ int prefixkv_decode_attn_evict(const pkv_shape* s, int l0, int l1, const void* q
     if (!aligned16(q) || !aligned16(kc) || !aligned16(vc) || !aligned16(out) || !aligned16(k_new) ||
         !aligned16(v_new))
         return PKV_ERR_STRIDE;
-    (void)ws; (void)ws_bytes;  // this stage needs no scratch
+    const size_t need = decode_ws_bytes(*s);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return PKV_ERR_WORKSPACE;
     const hipError_t e = launch_decode_evict(*s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, base_lens,
-                                             lens, kept_pos, t, distance, out, (hipStream_t)stream);
+                                             lens, kept_pos, t, distance, out, ws, (hipStream_t)stream);
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
 

@@ -22,6 +22,8 @@
 
 namespace pkv {
 
+static int pick_group(int grp) { return grp % 8 == 0 ? 8 : grp % 4 == 0 ? 4 : grp % 2 == 0 ? 2 : 1; }
+
 constexpr int kLenBits = 20;
 constexpr int kLenMask = (1 << kLenBits) - 1;
 
@@ -41,6 +43,9 @@ struct DecodeParams {
     int N, t, d;                  // prompt length, 1-based decode step, distance
     const int32_t* base_lens;     // [B,L] entries kept after prefill
     int32_t* kept_pos;            // one int per slot, may be null
+    // work list of the grouped-query kernel (see decode_plan_kernel)
+    int G, n_seg, S0, pieces_cap, record_word, partial_word;
+    int* plan;
 };
 
 // Virtual row numbering of a segment under pruning: rows [0, perm) are the permanent slots, rows
@@ -341,12 +346,174 @@ decode_attn_kernel(DecodeParams p) {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
+// Partial results cross workgroups (and XCDs) inside one launch: device-scope relaxed atomics go straight
+// to the coherent level and need no cache-wide write-back or invalidate.
+__device__ __forceinline__ void st_agent(float* p, float v) {
+    __hip_atomic_store((unsigned*)p, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+    return __uint_as_float(__hip_atomic_load((const unsigned*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
 __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// State of one segment for this step, computed identically by every workgroup that touches it.
+struct SegState {
+    int len_old;   // occupied slots before the step (under pruning: permanent entries)
+    int cap;
+    int len;       // rows to attend to in this step (virtual rows under pruning)
+    int len_next;  // value of lens after the step
+    int ring0, cs; // pruning: first ring slot, ring slot of the token decided in this step
+    bool app, grad, decide;
+    RingMap ring;
+    int64_t off;
+};
+
+template <bool EV>
+__device__ __forceinline__ SegState seg_state(const DecodeParams& p, int sl) {
+    SegState s;
+    s.len_old = __hip_atomic_load(p.lens + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kLenMask;
+    s.cap = p.caps[sl];
+    s.off = p.seg_off[sl];
+    s.app = p.append && s.len_old < s.cap;
+    s.len = s.len_old + (s.app ? 1 : 0);
+    s.len_next = s.len;
+    s.ring = {0, s.app ? s.len_old : -1, -1};
+    s.ring0 = 0; s.cs = 0; s.grad = false; s.decide = false;
+    if constexpr (EV) {
+        const int base = p.base_lens[sl];
+        s.ring0 = s.cap - (p.d + 1);
+        s.app = base >= 0 && s.ring0 >= base && s.len_old <= s.ring0;
+        s.decide = s.app && p.t > p.d;
+        s.cs = p.t % (p.d + 1);
+        long long target = (2ll * base * ((long long)p.N + p.t) + p.N) / (2ll * p.N);
+        target = target < 1 ? 1 : target;
+        s.grad = s.decide && (long long)s.len_old + p.d + 1 <= target && s.len_old < s.ring0;
+        s.ring.shift = s.ring0 - s.len_old;
+        s.ring.r_new = s.app ? s.len_old + (p.t - 1) % (p.d + 1) : -1;
+        s.ring.r_mask = (s.decide && !s.grad) ? s.len_old + s.cs : -1;
+        s.len = s.app ? s.len_old + (p.t < p.d + 1 ? p.t : p.d + 1) : 0;
+        s.len_next = s.len_old + (s.grad ? 1 : 0);
+    }
+    return s;
+}
+
+// Work list for the grouped-query kernel.  PrefixKV gives the layers very different lengths (tens of rows
+// next to thousands), so a segment is cut into pieces of S rows and every (piece, head group) is one
+// work item of similar size.  The planning kernel (one workgroup) evaluates the state of every segment
+// once, writes one 64-byte record per piece with everything the attention kernel needs, and advances
+// lens itself, so the attention kernel neither reads nor counts on lens.
+// Layout of the workspace, in 32-bit words:
+//   [0] next item to claim  [1] number of items  [2] S  [3] number of pieces  [4] number of full pieces
+//   [16 ...]  arrive[n_seg * HU], records[pieces_cap][16] (64-byte aligned),
+//   then the partial results of split segments: [pieces_cap * HU][G][D + 2] floats.
+// S starts at S0 and doubles until the pieces fit the table.
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanHdr = 16;
+constexpr int kRecWords = 16;
+enum { REC_SL = 0, REC_SPLIT, REC_NSPLIT, REC_FIRST, REC_LEN_OLD, REC_LEN, REC_CAP, REC_FLAGS, REC_OFF_LO,
+       REC_OFF_HI, REC_SHIFT, REC_RNEW, REC_RMASK, REC_RING0, REC_CS, REC_LAST };
+enum { RECF_APP = 1, RECF_GRAD = 2, RECF_DECIDE = 4 };
+
+constexpr int kPlanClasses = 16;
+// Size class of a segment's last piece: 0 for the longest remainders.
+__device__ __forceinline__ int last_piece_class(int len, int S) {
+    int np = (len + S - 1) / S;
+    np = np < 1 ? 1 : np;
+    const int rows = len - (np - 1) * S;                 // 0 .. S
+    const int c = (int)(((long long)rows * kPlanClasses) / ((long long)S + 1));   // 0 .. kPlanClasses-1
+    return kPlanClasses - 1 - c;
+}
+
+template <bool EV>
+__global__ void __launch_bounds__(kPlanThreads)
+decode_plan_kernel(DecodeParams p) {
+    __shared__ int s_red[kPlanThreads];
+    const int tid = threadIdx.x, n = p.n_seg;
+    const int per = (n + kPlanThreads - 1) / kPlanThreads;
+    const int lo = tid * per < n ? tid * per : n, hi = lo + per < n ? lo + per : n;
+    int* hdr = p.plan;
+    int* arrive = p.plan + kPlanHdr;
+    int* records = p.plan + p.record_word;
+    // Items are claimed from a counter in list order, so the list holds the full pieces first and the last
+    // (shorter) piece of every segment at the end: the tail of the launch is made of small items.
+    int S = p.S0, total_full = 0, mine = 0;
+    for (;;) {
+        mine = 0;
+        for (int i = lo; i < hi; ++i) {
+            const int sl = (i / p.nl) * p.L + p.l0 + i % p.nl;
+            const int len = seg_state<EV>(p, sl).len;
+            const int np = (len + S - 1) / S;
+            mine += np < 1 ? 0 : np - 1;      // full pieces; every segment has exactly one last piece
+        }
+        s_red[tid] = mine;
+        __syncthreads();
+        for (int st = kPlanThreads / 2; st > 0; st >>= 1) {
+            if (tid < st) s_red[tid] += s_red[tid + st];
+            __syncthreads();
+        }
+        total_full = s_red[0];
+        __syncthreads();
+        if (total_full + n <= p.pieces_cap || S >= (1 << 24)) break;
+        S *= 2;
+    }
+    // exclusive scan of the per-thread counts
+    s_red[tid] = mine;
+    __syncthreads();
+    for (int st = 1; st < kPlanThreads; st <<= 1) {
+        const int v = tid >= st ? s_red[tid - st] : 0;
+        __syncthreads();
+        s_red[tid] += v;
+        __syncthreads();
+    }
+    int at = s_red[tid] - mine;
+    const int total = total_full + n;
+    const bool ok = total <= p.pieces_cap;   // cannot fail for pieces_cap >= n_seg
+    // the last pieces go into the list by size class, largest first (the order inside a class is arbitrary;
+    // results do not depend on the order of the list)
+    __shared__ int s_cls[kPlanClasses];
+    if (tid < kPlanClasses) s_cls[tid] = 0;
+    __syncthreads();
+    for (int i = lo; i < hi; ++i) {
+        const int sl = (i / p.nl) * p.L + p.l0 + i % p.nl;
+        atomicAdd(&s_cls[last_piece_class(seg_state<EV>(p, sl).len, S)], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int c = 0; c < kPlanClasses; ++c) { const int v = s_cls[c]; s_cls[c] = run; run += v; }
+    }
+    __syncthreads();
+    if (ok) {
+        for (int i = lo; i < hi; ++i) {
+            const int sl = (i / p.nl) * p.L + p.l0 + i % p.nl;
+            const SegState ss = seg_state<EV>(p, sl);
+            int np = (ss.len + S - 1) / S;
+            np = np < 1 ? 1 : np;
+            const int last = total_full + atomicAdd(&s_cls[last_piece_class(ss.len, S)], 1);
+            for (int k = 0; k < np; ++k) {
+                int* r = records + (size_t)(k < np - 1 ? at + k : last) * kRecWords;
+                r[REC_SL] = sl; r[REC_SPLIT] = k; r[REC_NSPLIT] = np; r[REC_FIRST] = at;
+                r[REC_LEN_OLD] = ss.len_old; r[REC_LEN] = ss.len; r[REC_CAP] = ss.cap;
+                r[REC_FLAGS] = (ss.app ? RECF_APP : 0) | (ss.grad ? RECF_GRAD : 0) | (ss.decide ? RECF_DECIDE : 0);
+                r[REC_OFF_LO] = (int)(uint32_t)ss.off; r[REC_OFF_HI] = (int)(ss.off >> 32);
+                r[REC_SHIFT] = ss.ring.shift; r[REC_RNEW] = ss.ring.r_new; r[REC_RMASK] = ss.ring.r_mask;
+                r[REC_RING0] = ss.ring0; r[REC_CS] = ss.cs; r[REC_LAST] = last;
+            }
+            at += np - 1;
+            p.lens[sl] = ss.len_next;        // the records carry the old state; nobody else reads lens in this step
+        }
+    }
+    const int HU = p.H / p.G;
+    for (int i = tid; i < n * HU; i += kPlanThreads) arrive[i] = 0;
+    if (tid == 0) { hdr[0] = 0; hdr[1] = ok ? total * HU : 0; hdr[2] = S; hdr[3] = ok ? total : 0; hdr[4] = total_full; }
+}
+
+// Persistent kernel: as many workgroups as fit on the chip, each taking every gridDim-th item of the list.
 template <int D, int G, int NT, int W, int OCC, bool EV>
 __global__ void __launch_bounds__(W * kWave, OCC)
 decode_gqa_kernel(DecodeParams p) {
@@ -358,49 +525,46 @@ decode_gqa_kernel(DecodeParams p) {
     constexpr int GP = G < 4 ? 4 : G;            // head columns kept in LDS
     constexpr int DMAX = 128;
     constexpr int ROWB = D * 2;
+    constexpr int PST = D + 2;                   // floats per (item, head) partial: numerators, max, denominator
     static_assert(D == 64 || D == 128, "head dimension");
-    __shared__ float s_part[W][G][DMAX + 2];
+    __shared__ float s_part[2][W][G][DMAX + 2];   // double-buffered across items: no barrier at the end of an item
     __shared__ __attribute__((aligned(16))) float s_p[W][BR * GP];
     __shared__ __attribute__((aligned(16))) float s_corr[W][GP];
+    __shared__ int s_last[2];
+    __shared__ int s_next[2];
 
     const int HU = p.H / G;
-    const int hu = blockIdx.x % HU, i_seg = blockIdx.x / HU;
-    const int b = i_seg / p.nl, l = p.l0 + i_seg % p.nl, sl = b * p.L + l;
     const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
     const int sub = lane % LPR, rg = lane / LPR;     // V layout
     const int kr = lane & 15, kq = lane >> 4;        // K / score layout: row (or head) kr, quad kq
+    int* hdr = p.plan;
+    int* arrive = p.plan + kPlanHdr;
+    const int* records = p.plan + p.record_word;
+    float* partial = (float*)(p.plan + p.partial_word);
+    const int total = hdr[1], S = hdr[2];
 
-    const int len_old = __hip_atomic_load(p.lens + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kLenMask;
-    const int cap = p.caps[sl];
-    const int64_t off = p.seg_off[sl];
-    bool app = p.append && len_old < cap;
-    int len = len_old + (app ? 1 : 0), len_next = len;
-    RingMap ring = {0, app ? len_old : -1, -1};
-    int ring0 = 0, cs = 0;
-    bool grad = false, decide = false;
-    if constexpr (EV) {
-        const int base = p.base_lens[sl];
-        ring0 = cap - (p.d + 1);
-        app = base >= 0 && ring0 >= base && len_old <= ring0;
-        decide = app && p.t > p.d;
-        cs = p.t % (p.d + 1);
-        long long target = (2ll * base * ((long long)p.N + p.t) + p.N) / (2ll * p.N);
-        target = target < 1 ? 1 : target;
-        grad = decide && (long long)len_old + p.d + 1 <= target && len_old < ring0;
-        ring.shift = ring0 - len_old;
-        ring.r_new = app ? len_old + (p.t - 1) % (p.d + 1) : -1;
-        ring.r_mask = (decide && !grad) ? len_old + cs : -1;
-        len = app ? len_old + (p.t < p.d + 1 ? p.t : p.d + 1) : 0;
-        len_next = len_old + (grad ? 1 : 0);
-    }
-    const int nblk = (len + BR - 1) / BR;
+  // every workgroup starts with the item of its own index and claims further ones from a counter; the claim
+  // for the next item is issued first, so its round trip is hidden behind the work on this one
+  for (int item = blockIdx.x, it = 0; item < total; ++it) {
+    if (threadIdx.x == 0) s_next[it & 1] = atomicAdd(hdr, 1) + (int)gridDim.x;
+    const int piece = item / HU, hu = item % HU;
+    const int* rec = records + (size_t)piece * kRecWords;
+    const int sl = rec[REC_SL], split = rec[REC_SPLIT], nsplit = rec[REC_NSPLIT], first_full = rec[REC_FIRST];
+    const int len_old = rec[REC_LEN_OLD], len = rec[REC_LEN], cap = rec[REC_CAP], flags = rec[REC_FLAGS];
+    const int64_t seg_tok = (int64_t)(((uint64_t)(uint32_t)rec[REC_OFF_HI] << 32) | (uint32_t)rec[REC_OFF_LO]);
+    const RingMap ring = {rec[REC_SHIFT], rec[REC_RNEW], rec[REC_RMASK]};
+    const int l = sl % p.L;
+    const int row_lo = split * S;
+    const int row_hi = len < row_lo + S ? len : row_lo + S;
+    const int nblk = row_hi > row_lo ? (row_hi - row_lo + BR - 1) / BR : 0;
     const int kvh = (hu * G) / p.grp;
-    const bool writer = app && ((hu * G) % p.grp == 0);
-    const int64_t segbase = (off * p.Hkv + (int64_t)kvh * cap) * ROWB;
+    const bool writer = (flags & RECF_APP) && ((hu * G) % p.grp == 0);
+    const int64_t segbase = (seg_tok * p.Hkv + (int64_t)kvh * cap) * ROWB;
     const unsigned char* knew = p.k_new + ((int64_t)sl * p.Hkv + kvh) * ROWB;
     const unsigned char* vnew = p.v_new + ((int64_t)sl * p.Hkv + kvh) * ROWB;
     unsigned char* kseg = p.kc + segbase;
     unsigned char* vseg = p.vc + segbase;
+    float (*spart)[G][DMAX + 2] = s_part[it & 1];
 
     float o[G][8], m_run = -INFINITY, l_run = 0.f;
 #pragma unroll
@@ -420,7 +584,7 @@ decode_gqa_kernel(DecodeParams p) {
         float* ps = s_p[wv];
         float* cr = s_corr[wv];
         for (int blk = wv; blk < nblk; blk += W) {
-            const int r0 = blk * BR;
+            const int r0 = row_lo + blk * BR;
             const bool full = r0 + BR <= len_old;
             if constexpr (EV) {
                 const int hi = len < r0 + BR ? len : r0 + BR;
@@ -545,17 +709,20 @@ decode_gqa_kernel(DecodeParams p) {
                 for (int x = 0; x < 8; ++x) o[g][x] += __shfl_xor(o[g][x], sh, kWave);
     }
     if constexpr (EV) {
-        if (grad && writer && wv == 0 && rg == 0) {
-            const size_t src = (size_t)(ring0 + cs) * ROWB + sub * 16, dst = (size_t)len_old * ROWB + sub * 16;
-            *(uint4*)(kseg + dst) = *(const uint4*)(kseg + src);
-            *(uint4*)(vseg + dst) = *(const uint4*)(vseg + src);
-        }
-        if (p.kept_pos && app && hu == 0 && threadIdx.x == 0) {
-            int32_t* kp = p.kept_pos + off;
-            kp[ring0 + (p.t - 1) % (p.d + 1)] = p.N + p.t - 1;
-            if (decide) {
-                if (grad) kp[len_old] = p.N + p.t - p.d - 1;
-                kp[ring0 + cs] = -1;
+        if (split == 0) {
+            const int ring0 = rec[REC_RING0], cs = rec[REC_CS];
+            if ((flags & RECF_GRAD) && writer && wv == 0 && rg == 0) {
+                const size_t src = (size_t)(ring0 + cs) * ROWB + sub * 16, dst = (size_t)len_old * ROWB + sub * 16;
+                *(uint4*)(kseg + dst) = *(const uint4*)(kseg + src);
+                *(uint4*)(vseg + dst) = *(const uint4*)(vseg + src);
+            }
+            if (p.kept_pos && (flags & RECF_APP) && hu == 0 && threadIdx.x == 0) {
+                int32_t* kp = p.kept_pos + seg_tok;
+                kp[ring0 + (p.t - 1) % (p.d + 1)] = p.N + p.t - 1;
+                if (flags & RECF_DECIDE) {
+                    if (flags & RECF_GRAD) kp[len_old] = p.N + p.t - p.d - 1;
+                    kp[ring0 + cs] = -1;
+                }
             }
         }
     }
@@ -563,37 +730,72 @@ decode_gqa_kernel(DecodeParams p) {
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int x = 0; x < 8; ++x) s_part[wv][g][sub * 8 + x] = o[g][x];
+            for (int x = 0; x < 8; ++x) spart[wv][g][sub * 8 + x] = o[g][x];
     }
-    if (kq == 0 && kr < G) { s_part[wv][kr][DMAX] = m_run; s_part[wv][kr][DMAX + 1] = l_run; }
+    if (kq == 0 && kr < G) { spart[wv][kr][DMAX] = m_run; spart[wv][kr][DMAX + 1] = l_run; }
     __syncthreads();
+    const int item_next = __builtin_amdgcn_readfirstlane(s_next[it & 1]);   // uniform, stays in scalar registers
+    // merge the wavefronts: thread (g, d).  A whole segment is written out; a piece leaves (numerators,
+    // max, denominator) in the workspace and the last piece of the (segment, head group) to arrive adds them up
+    float* mine = partial + ((size_t)piece * HU + hu) * (G * PST);
     for (int i = threadIdx.x; i < G * D; i += blockDim.x) {
         const int g = i / D, d = i % D;
         float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < W; ++w) M = fmaxf(M, s_part[w][g][DMAX]);
+        for (int w = 0; w < W; ++w) M = fmaxf(M, spart[w][g][DMAX]);
         float num = 0.f, den = 0.f;
         if (M > -INFINITY) {
 #pragma unroll
             for (int w = 0; w < W; ++w) {
-                const float wgt = __builtin_amdgcn_exp2f(s_part[w][g][DMAX] - M);
-                num = fmaf(wgt, s_part[w][g][d], num);
-                den = fmaf(wgt, s_part[w][g][DMAX + 1], den);
+                const float wgt = __builtin_amdgcn_exp2f(spart[w][g][DMAX] - M);
+                num = fmaf(wgt, spart[w][g][d], num);
+                den = fmaf(wgt, spart[w][g][DMAX + 1], den);
             }
         }
-        const float r = den > 0.f ? num / den : 0.f;
-        ((bf16_t*)p.out)[((size_t)sl * p.H + hu * G + g) * D + d] = f32_to_bf16(r);
+        if (nsplit == 1) {
+            const float r = den > 0.f ? num / den : 0.f;   // an empty segment gives zeros
+            ((bf16_t*)p.out)[((size_t)sl * p.H + hu * G + g) * D + d] = f32_to_bf16(r);
+        } else {
+            st_agent(mine + g * PST + d, num);
+            if (d == 0) { st_agent(mine + g * PST + D, M); st_agent(mine + g * PST + D + 1, den); }
+        }
     }
-    if (threadIdx.x == 0) {
-        const int old = atomicAdd(p.lens + sl, 1 << kLenBits);
-        if ((int)((unsigned)old >> kLenBits) == HU - 1)
-            __hip_atomic_store(p.lens + sl, len_next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (nsplit > 1) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the partial has been written before the arrival counts
+        __syncthreads();
+        const int i_seg = (sl / p.L) * p.nl + (sl % p.L - p.l0);
+        if (threadIdx.x == 0) s_last[it & 1] = atomicAdd(arrive + i_seg * HU + hu, 1) == nsplit - 1;
+        __syncthreads();
+        if (s_last[it & 1]) {
+            // the partial of piece k sits at the piece's place in the list
+            const int last_piece = rec[REC_LAST];
+            for (int i = threadIdx.x; i < G * D; i += blockDim.x) {
+                const int g = i / D, d = i % D;
+                float M = -INFINITY;
+                for (int k = 0; k < nsplit; ++k) {
+                    const int pc = k < nsplit - 1 ? first_full + k : last_piece;
+                    M = fmaxf(M, ld_agent(partial + ((size_t)pc * HU + hu) * (G * PST) + g * PST + D));
+                }
+                float num = 0.f, den = 0.f;
+                if (M > -INFINITY) {
+                    for (int k = 0; k < nsplit; ++k) {
+                        const int pc = k < nsplit - 1 ? first_full + k : last_piece;
+                        const float* pk = partial + ((size_t)pc * HU + hu) * (G * PST) + g * PST;
+                        const float wgt = __builtin_amdgcn_exp2f(ld_agent(pk + D) - M);
+                        num = fmaf(wgt, ld_agent(pk + d), num);
+                        den = fmaf(wgt, ld_agent(pk + D + 1), den);
+                    }
+                }
+                const float r = den > 0.f ? num / den : 0.f;
+                ((bf16_t*)p.out)[((size_t)sl * p.H + hu * G + g) * D + d] = f32_to_bf16(r);
+            }
+        }
     }
+    item = item_next;
+  }
 }
 
-size_t decode_ws_bytes(const pkv_shape&) { return 0; }
 
-static int pick_group(int grp) { return grp % 8 == 0 ? 8 : grp % 4 == 0 ? 4 : grp % 2 == 0 ? 2 : 1; }
 
 // Launch shapes.  All workgroups of a launch should be resident at once (one round), so short
 // segments get small workgroups with many row loads in flight per wavefront, and long segments get
@@ -652,36 +854,59 @@ static hipError_t launch_decode_g(const DecodeParams& p, int G, int shape, int n
     }
 }
 
-// Grouped-query bf16 launches: W wavefronts per workgroup by segment length, 64-row blocks.
+// Workspace layout of the grouped-query path for n_seg segments (see decode_plan_kernel).
+struct GqaLayout {
+    int pieces_cap, record_word, partial_word;
+    size_t bytes;
+};
+static GqaLayout gqa_layout(int n_seg, int H, int G, int D, int N) {
+    GqaLayout g;
+    const int HU = H / G;
+    g.pieces_cap = n_seg * (2 + N / 512);
+    g.record_word = (int)(((size_t)kPlanHdr + (size_t)n_seg * HU + 15) / 16 * 16);
+    g.partial_word = g.record_word + g.pieces_cap * kRecWords;
+    g.bytes = ((size_t)g.partial_word + (size_t)g.pieces_cap * HU * G * (D + 2)) * 4;
+    return g;
+}
+
+size_t decode_ws_bytes(const pkv_shape& s) {
+    const int G = pick_group(s.H / s.Hkv);
+    if (s.dtype != PKV_BF16 || G < 2) return 0;
+    return gqa_layout(s.B * s.L, s.H, G, s.D, s.N).bytes;
+}
+
+// Grouped-query bf16 launches: the planning kernel, then one resident round of workgroups of W wavefronts
+// (2 wavefronts per SIMD) that claim (piece, head group) items until the list is empty.
 template <int D, int G, bool EV>
-static hipError_t launch_gqa_s(const DecodeParams& p, int shape, int nblk, hipStream_t st) {
-    if (shape == 0)
-        hipLaunchKernelGGL((decode_gqa_kernel<D, G, 4, 2, 2, EV>), dim3(nblk), dim3(2 * kWave), 0, st, p);
-    else if (shape == 1)
-        hipLaunchKernelGGL((decode_gqa_kernel<D, G, 4, 4, 2, EV>), dim3(nblk), dim3(4 * kWave), 0, st, p);
-    else
-        hipLaunchKernelGGL((decode_gqa_kernel<D, G, 4, 8, 2, EV>), dim3(nblk), dim3(8 * kWave), 0, st, p);
+static hipError_t launch_gqa_s(DecodeParams p, const pkv_shape& s, int* ws, hipStream_t st) {
+    constexpr int W = 4;
+    const GqaLayout lay = gqa_layout(s.B * p.nl, s.H, G, D, s.N);
+    p.G = G; p.n_seg = s.B * p.nl; p.S0 = 1024; p.pieces_cap = lay.pieces_cap; p.record_word = lay.record_word; p.partial_word = lay.partial_word;
+    p.plan = ws;
+    hipLaunchKernelGGL((decode_plan_kernel<EV>), dim3(1), dim3(kPlanThreads), 0, st, p);
+    int grid = compute_units() * (8 / W);
+    const long long most = (long long)lay.pieces_cap * (s.H / G);
+    if (grid > most) grid = (int)most;
+    hipLaunchKernelGGL((decode_gqa_kernel<D, G, 4, W, 2, EV>), dim3(grid), dim3(W * kWave), 0, st, p);
     return hipGetLastError();
 }
 
 template <int D, bool EV>
-static hipError_t launch_gqa(const DecodeParams& p, int G, int shape, int nblk, hipStream_t st) {
+static hipError_t launch_gqa(const DecodeParams& p, const pkv_shape& s, int G, int* ws, hipStream_t st) {
     switch (G) {
-        case 8: return launch_gqa_s<D, 8, EV>(p, shape, nblk, st);
-        case 4: return launch_gqa_s<D, 4, EV>(p, shape, nblk, st);
-        default: return launch_gqa_s<D, 2, EV>(p, shape, nblk, st);
+        case 8: return launch_gqa_s<D, 8, EV>(p, s, ws, st);
+        case 4: return launch_gqa_s<D, 4, EV>(p, s, ws, st);
+        default: return launch_gqa_s<D, 2, EV>(p, s, ws, st);
     }
 }
 
 template <bool EV>
-static hipError_t launch_decode_any(const pkv_shape& s, const DecodeParams& p, hipStream_t st) {
+static hipError_t launch_decode_any(const pkv_shape& s, const DecodeParams& p, void* ws, hipStream_t st) {
     const int G = pick_group(p.grp);
     const int nblk = s.B * p.nl * (s.H / G);
     const bool bf16 = s.dtype == PKV_BF16;
-    if (bf16 && G >= 2) {   // several query heads share the cached rows: scores on the matrix cores
-        const int shp = s.N <= 1024 ? 0 : s.N <= 4096 ? 1 : 2;
-        return s.D == 128 ? launch_gqa<128, EV>(p, G, shp, nblk, st) : launch_gqa<64, EV>(p, G, shp, nblk, st);
-    }
+    if (bf16 && G >= 2)     // several query heads share the cached rows: scores on the matrix cores
+        return s.D == 128 ? launch_gqa<128, EV>(p, s, G, (int*)ws, st) : launch_gqa<64, EV>(p, s, G, (int*)ws, st);
     const int lpr = s.D * (bf16 ? 2 : 4) / 16;
     const int shape = s.N <= 1024 ? 0 : s.N <= 4096 ? 1 : 2;   // segments hold at most N + appended tokens
     if (bf16) {
@@ -703,24 +928,26 @@ static DecodeParams make_params(const pkv_shape& s, int l0, int l1, const void* 
     p.kc = (unsigned char*)kc; p.vc = (unsigned char*)vc; p.seg_off = seg_off; p.caps = caps;
     p.lens = lens; p.out = (unsigned char*)out;
     p.N = s.N; p.t = 0; p.d = 0; p.base_lens = nullptr; p.kept_pos = nullptr;
+    p.G = 1; p.n_seg = 0; p.S0 = 0; p.pieces_cap = 0; p.record_word = 0; p.partial_word = 0; p.plan = nullptr;
     return p;
 }
 
 hipError_t launch_decode(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
                          const void* v_new, const float* scale, void* kc, void* vc,
-                         const int64_t* seg_off, const int32_t* caps, int32_t* lens, void* out,
+                         const int64_t* seg_off, const int32_t* caps, int32_t* lens, void* out, void* ws,
                          hipStream_t st) {
     const DecodeParams p = make_params(s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, lens, out);
-    return launch_decode_any<false>(s, p, st);
+    return launch_decode_any<false>(s, p, ws, st);
 }
 
 hipError_t launch_decode_evict(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
                                const void* v_new, const float* scale, void* kc, void* vc,
                                const int64_t* seg_off, const int32_t* caps, const int32_t* base_lens,
-                               int32_t* lens, int32_t* kept_pos, int t, int d, void* out, hipStream_t st) {
+                               int32_t* lens, int32_t* kept_pos, int t, int d, void* out, void* ws,
+                               hipStream_t st) {
     DecodeParams p = make_params(s, l0, l1, q, k_new, v_new, scale, kc, vc, seg_off, caps, lens, out);
     p.t = t; p.d = d; p.base_lens = base_lens; p.kept_pos = kept_pos;
-    return launch_decode_any<true>(s, p, st);
+    return launch_decode_any<true>(s, p, ws, st);
 }
 
 }  // namespace pkv

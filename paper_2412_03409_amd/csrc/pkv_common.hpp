@@ -60,11 +60,12 @@ hipError_t launch_compact(const pkv_shape& s, const void* k, Strides ks, const v
 size_t decode_ws_bytes(const pkv_shape& s);
 hipError_t launch_decode(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
                          const void* v_new, const float* scale, void* kc, void* vc,
-                         const int64_t* seg_off, const int32_t* caps, int32_t* lens, void* out,
+                         const int64_t* seg_off, const int32_t* caps, int32_t* lens, void* out, void* ws,
                          hipStream_t st);
 hipError_t launch_decode_evict(const pkv_shape& s, int l0, int l1, const void* q, const void* k_new,
                                const void* v_new, const float* scale, void* kc, void* vc,
                                const int64_t* seg_off, const int32_t* caps, const int32_t* base_lens,
-                               int32_t* lens, int32_t* kept_pos, int t, int d, void* out, hipStream_t st);
+                               int32_t* lens, int32_t* kept_pos, int t, int d, void* out, void* ws,
+                               hipStream_t st);
 
 }  // namespace pkv

@@ -50,6 +50,8 @@ class HotPath:
             lens=torch.empty((Bn, L), dtype=torch.int32, device=dev),
             cache_tokens=self.cache_tokens, Hkv=Hkv, D=D)
         self.out = torch.empty((max(self.T, 1), Bn, L, H, D), dtype=dt, device=dev)
+        self.dec_ws = torch.empty(max(256, B_.prefixkv_workspace_bytes(B_.OP_DECODE, Bn, L, H, Hkv, N, D, code)),
+                                  dtype=torch.uint8, device=dev)
         self._graph: Optional[torch.cuda.CUDAGraph] = None
 
     # ---- the four C-ABI calls, on pre-allocated buffers ------------------------------------------
@@ -67,8 +69,9 @@ class HotPath:
     def run_decode_step(self, t: int, dq, dk, dv):
         if self.evict_distance is not None:
             return B_.prefixkv_decode_attn_evict(self.cache, self.sel.lengths, dq[t], dk[t], dv[t], self.scale,
-                                                 self.N, t + 1, self.evict_distance, out=self.out[t])
-        return B_.prefixkv_decode_attn(self.cache, dq[t], dk[t], dv[t], self.scale, self.N, out=self.out[t])
+                                                 self.N, t + 1, self.evict_distance, out=self.out[t], ws=self.dec_ws)
+        return B_.prefixkv_decode_attn(self.cache, dq[t], dk[t], dv[t], self.scale, self.N, out=self.out[t],
+                                       ws=self.dec_ws)
 
     def run_decode_loop(self, dq, dk, dv):
         for t in range(self.T):

@@ -129,6 +129,12 @@ def test_compact_and_decode_argument_errors():
     assert dec(l1=5) == 2
     assert dec(sh=_shape(H=4096, Hkv=2)) == 2
     assert dec(q=C.c_void_p(0x1008)) == 4
+    gqa = _shape(H=32, Hkv=8, dtype=P.PKV_BF16)   # grouped-query bf16: the work list lives in the workspace
+    need = P.prefixkv_workspace_bytes(Bd.OP_DECODE, gqa.B, gqa.L, gqa.H, gqa.Hkv, gqa.N, gqa.D, gqa.dtype)
+    assert need > 0
+    assert dec(sh=gqa) == 5
+    assert lib.prefixkv_decode_attn(C.byref(gqa), 0, 4, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                    FAKE, need - 1, None) == 5
     ev = lambda t=1, d=4, kn=FAKE, base=FAKE, kp=None, sh=s: lib.prefixkv_decode_attn_evict(
         C.byref(sh), 0, 4, FAKE, kn, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, base, FAKE, kp, t, d, FAKE, None, 0,
         None)
