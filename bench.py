@@ -157,7 +157,8 @@ def main() -> int:
     if os.path.exists(tpath):
         key = f"decode_attn_kernel/{w.name}/budget{r:g}" + ("" if d_ev is None else f"/evict{d_ev}")
         traffic = json.load(open(tpath)).get(key)
-    roofline = {"kernel": "decode_attn_kernel", "bound": "hbm", "achieved": round(achieved, 1),
+    gqa = w.dtype == "bf16" and (w.H // w.Hkv) % 2 == 0
+    roofline = {"kernel": "decode_plan_kernel + decode_gqa_kernel" if gqa else "decode_attn_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "bytes_per_launch": int(alg_bytes), "kernel_ms": round(kern_ms, 5),
                 "launches_per_step": T,

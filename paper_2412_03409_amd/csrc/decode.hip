@@ -846,12 +846,15 @@ static hipError_t launch_decode_s(const DecodeParams& p, int shape, int nblk, hi
 
 template <bool BF16, int LPR, bool EV>
 static hipError_t launch_decode_g(const DecodeParams& p, int G, int shape, int nblk, hipStream_t st) {
-    switch (G) {
-        case 8: return launch_decode_s<BF16, LPR, 8, EV>(p, shape, nblk, st);
-        case 4: return launch_decode_s<BF16, LPR, 4, EV>(p, shape, nblk, st);
-        case 2: return launch_decode_s<BF16, LPR, 2, EV>(p, shape, nblk, st);
-        default: return launch_decode_s<BF16, LPR, 1, EV>(p, shape, nblk, st);
+    if constexpr (!BF16) {   // bf16 caches with several query heads per KV head use decode_gqa_kernel instead
+        switch (G) {
+            case 8: return launch_decode_s<BF16, LPR, 8, EV>(p, shape, nblk, st);
+            case 4: return launch_decode_s<BF16, LPR, 4, EV>(p, shape, nblk, st);
+            case 2: return launch_decode_s<BF16, LPR, 2, EV>(p, shape, nblk, st);
+            default: break;
+        }
     }
+    return launch_decode_s<BF16, LPR, 1, EV>(p, shape, nblk, st);
 }
 
 // Workspace layout of the grouped-query path for n_seg segments (see decode_plan_kernel).
