@@ -443,6 +443,7 @@ def test_decode_evict_without_position_tracking_and_capacity_guard():
 
 def test_decode_layer_range_and_rejected_sequence():
     run_decode_case(2, 4, 4, 4, 100, 128, torch.bfloat16, 0.3, 2, seed=7, layer_range=(1, 3))
+    run_decode_case(2, 4, 8, 2, 1300, 128, torch.bfloat16, 0.9, 2, seed=9, layer_range=(1, 3))   # grouped, split
     run_decode_case(2, 3, 4, 2, 100, 128, torch.bfloat16, 0.3, 2, seed=8, zero_seq=True)
 
 
@@ -487,13 +488,21 @@ def test_tiny_config_end_to_end():
     check_cache(cache, o_cache, torch.float32)
 
 
-def test_decode_loop_graph_replays_match_eager():
+@pytest.mark.parametrize("variant", ["tiny", "gqa_split", "gqa_pruning"])
+def test_decode_loop_graph_replays_match_eager(variant):
     # the decode loop captured as one HIP graph: several replays, with eager work and synchronisations
-    # between them, must each reproduce the eager outputs and the final cache bit for bit
+    # between them, must each reproduce the eager outputs and the final cache bit for bit.  The grouped-query
+    # variants run the planning kernel + work-list kernel pair, with segments long enough to be split.
     from paper_2412_03409_amd.pipeline import HotPath
-    w = CONFIGS["tiny"].with_(decode_steps=6)
+    ev = None
+    if variant == "tiny":
+        w = CONFIGS["tiny"].with_(decode_steps=6)
+    else:
+        w = CONFIGS["gqa_long"].with_(B=1, L=3, N=2600, decode_steps=5, budget=0.7)
+        ev = 2 if variant == "gqa_pruning" else None
     x, dec = make_prefill(w), make_decode(w)
-    hp = HotPath(x["q"].to(DEV), x["k"].to(DEV), x["v"].to(DEV), x["scale"].to(DEV), w.budget_tokens(), w.decode_steps)
+    hp = HotPath(x["q"].to(DEV), x["k"].to(DEV), x["v"].to(DEV), x["scale"].to(DEV), w.budget_tokens(), w.decode_steps,
+                 evict_distance=ev)
     dq, dk, dv = dec["q"].to(DEV), dec["k"].to(DEV), dec["v"].to(DEV)
     hp.run_importance(); hp.run_select(); hp.run_compact()
     hp.run_decode_loop(dq, dk, dv)
