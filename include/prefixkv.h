@@ -11,13 +11,15 @@
  *     The library never allocates, frees or synchronises.  All work is enqueued on `stream`
  *     (a hipStream_t passed as void*; NULL = the default stream) and may still be running when the
  *     call returns.  Scratch space comes from the caller: `ws` [dev], `ws_bytes` >= the value of
- *     prefixkv_workspace_bytes() for the same arguments; its contents are undefined afterwards.
+ *     prefixkv_workspace_bytes() for the same arguments; its contents are undefined afterwards
+ *     and nothing is carried in it from one call to the next.
  *   - The return value reports ARGUMENT errors synchronously (pkv_status); nothing is enqueued
  *     when it is non-zero.  Data-dependent problems are reported through device status words.
  *   - Layouts are row-major with the head dimension D contiguous.  Where strides are given they
  *     are in ELEMENTS.  D is 64 or 128, H % Hkv == 0, 1 <= L <= 64, 1 <= N <= 8192, B >= 1.
  *   - Calls that use the same workspace or the same output buffers must be ordered by the
- *     caller (same stream, or events).  There is no global state.
+ *     caller (same stream, or events).  The library keeps no state between calls (apart from the
+ *     device's compute-unit count, looked up once).
  */
 #ifndef PREFIXKV_H
 #define PREFIXKV_H
@@ -64,8 +66,8 @@ int prefixkv_version(void);
 const char *prefixkv_status_string(int status);
 
 /* Workspace bytes for op = PKV_OP_*.  `has_lse` (PKV_OP_IMPORTANCE only) = the caller will pass
- * its own lse.  Returns 0 for invalid arguments and for stages that need no scratch (compaction
- * and decode attention: their ws may be NULL). */
+ * its own lse.  Returns 0 for invalid arguments and for stages that need no scratch (compaction;
+ * decode attention unless several query heads share a KV head in a bf16 cache): ws may then be NULL. */
 enum { PKV_OP_IMPORTANCE = 0, PKV_OP_SELECT = 1, PKV_OP_COMPACT = 2, PKV_OP_DECODE = 3 };
 size_t prefixkv_workspace_bytes(int op, const pkv_shape *shape, int has_lse);
 

@@ -337,6 +337,10 @@ def run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed, layer_range=No
     (1, 2, 4, 4, 1500, 128, torch.bfloat16, 0.7, 2),    # N > 1024: 4-wavefront launch shape
     (1, 2, 8, 2, 4200, 128, torch.bfloat16, 0.8, 2),    # N > 4096: 8-wavefront launch shape, GQA
     (1, 1, 2, 2, 5000, 64, torch.float32, 0.9, 1),      # long fp32 segment
+    (1, 2, 4, 2, 3000, 128, torch.bfloat16, 0.9, 2),    # grouped (2 heads per KV head), segments split in 3 pieces
+    (1, 2, 16, 2, 2500, 64, torch.bfloat16, 0.95, 2),   # grouped (8 heads), D = 64, split segments
+    (2, 3, 8, 2, 1100, 128, torch.bfloat16, 0.95, 3),   # the appended row crosses a piece boundary (1024)
+    (1, 1, 8, 1, 8192, 128, torch.bfloat16, 1.0, 1),    # grouped (8 heads), one segment of 8 pieces
 ])
 def test_decode_matches_oracle(B, L, H, Hkv, N, D, dtype, frac, steps):
     run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed=N + H)
@@ -398,6 +402,9 @@ def run_evict_case(B, L, H, Hkv, N, D, dtype, frac, d, steps, seed, extra=None, 
     (1, 2, 4, 4, 1500, 128, torch.bfloat16, 0.7, 6, 10),  # 4-wavefront launch shape
     (1, 2, 8, 2, 4200, 128, torch.bfloat16, 0.8, 3, 6),   # 8-wavefront launch shape, GQA
     (1, 3, 2, 2, 64, 64, torch.float32, 0.06, 63, 70),    # one kept entry per layer: sliding window
+    (1, 2, 8, 2, 1500, 128, torch.bfloat16, 0.6, 700, 12),  # grouped: the ring rows straddle a piece boundary
+    (1, 2, 4, 2, 2100, 128, torch.bfloat16, 0.95, 3, 8),    # grouped, split permanent region, survivors
+    (1, 2, 16, 2, 300, 64, torch.bfloat16, 0.5, 40, 60),    # grouped (8 heads), D = 64, ring longer than the kept part
 ])
 def test_decode_evict_matches_oracle(B, L, H, Hkv, N, D, dtype, frac, d, steps):
     run_evict_case(B, L, H, Hkv, N, D, dtype, frac, d, steps, seed=N + H + d)
