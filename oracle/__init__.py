@@ -198,6 +198,27 @@ def decode_attn_evict(cache, base_lens, q, k_new, v_new, scale, N: int, t: int, 
     return out
 
 
+def gini(cum):
+    """cum [B,L,N] u64 (from select/rank) -> Gini coefficient of every layer's priority sequence [B,L] f64."""
+    cum = np.ascontiguousarray(cum, dtype=np.uint64)
+    B, L, N = cum.shape
+    out = np.zeros((B, L), dtype=np.float64)
+    lib().pkvo_gini(C.c_long(B * L), N, _p(cum), _p(out))
+    return out
+
+
+def merge_position(cache, k, v, storage_bf16: bool = False):
+    """Average every pruned position into the nearest kept one, in place on a cache dict from compact()
+    (before any decode step).  k, v [B,L,Hkv,N,D] are the uncompressed tensors."""
+    k, v = _f32(k), _f32(v)
+    B, L, Hkv, N, D = k.shape
+    assert v.shape == k.shape and cache["Hkv"] == Hkv and cache["D"] == D
+    lib().pkvo_merge_position(B, L, Hkv, N, D, _p(k), _p(v), _p(cache["seg_off"]), _p(cache["caps"]),
+                              _p(cache["kept_pos"]), _p(cache["lens"]), _p(cache["kc"]), _p(cache["vc"]),
+                              int(storage_bf16))
+    return cache
+
+
 def segment(cache, name: str, b: int, l: int):
     """View of segment (b,l) of 'kc'/'vc' as [Hkv, cap, D], or of 'kept_pos' as [cap]."""
     off = int(cache["seg_off"][b, l])

@@ -517,3 +517,76 @@ int pkvo_decode_attn_evict(int B, int L, int H, int Hkv, int N, int D, int l0, i
         }
     return 0;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * Gini coefficient of a layer's priority sequence (Sec. 4.3, "Relation between KV cache size and
+ * importance distribution": layers with a more concentrated importance distribution, i.e. a higher
+ * Gini coefficient, get smaller caches).  With the Lorenz curve through the points
+ * (j/N, share of the j smallest weights) and the trapezoid rule, G = 1 - 2 * area under the curve.
+ * On the exact fixed-point cumulative sums C_k of the descending sequence (C_N = T) this is
+ *   G = (2 * (C_1 + ... + C_N) / T - N - 1) / N,
+ * 0 for a flat layer and (N-1)/N when one position holds everything.  T = 0 gives 0.
+ * cum [B*L][N] u64 -> gini [B*L] f64.
+ * ------------------------------------------------------------------------------------------- */
+void pkvo_gini(long segs, int N, const uint64_t *cum, double *gini) {
+    for (long s = 0; s < segs; ++s) {
+        const uint64_t *c = cum + (size_t)s * N;
+        unsigned __int128 S = 0;
+        for (int k = 0; k < N; ++k) S += c[k];
+        const double T = (double)c[N - 1];
+        gini[s] = T > 0.0 ? (2.0 * ((double)S / T) - (double)N - 1.0) / (double)N : 0.0;
+    }
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Cache merging by positional distance (Sec. 4.3, "Eviction or merging", the variant called
+ * "Position": matching metric c^{mn} = -|m - n|).  Every pruned position m of a layer is matched to
+ * the retained position n with the largest metric, i.e. the nearest one (a pruned position half way
+ * between two retained ones goes to the lower: the first maximum), and every retained vector is
+ * replaced by the average of itself and the pruned vectors matched to it; keys and values of all
+ * heads alike.  Works in place on a cache produced by pkvo_compact: slot j of segment (b,l) holds
+ * position kept_pos[j]; only the first lens[b,l] slots are touched.  The average is taken in fp64
+ * and, if storage_bf16, rounded to bfloat16 like every stored vector.
+ * k, v [B,L,Hkv,N,D] are the uncompressed tensors.
+ * ------------------------------------------------------------------------------------------- */
+void pkvo_merge_position(int B, int L, int Hkv, int N, int D, const float *k, const float *v,
+                         const int64_t *seg_off, const int32_t *caps, const int32_t *kept_pos,
+                         const int32_t *lens, float *kc, float *vc, int storage_bf16) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long bl = 0; bl < (long)B * L; ++bl) {
+        const int n = lens[bl], cap = caps[bl];
+        if (n <= 0) continue;
+        const int32_t *kp = kept_pos + seg_off[bl];
+        int *match = (int *)malloc(sizeof(int) * (size_t)N); /* slot every position is averaged into */
+        for (int m = 0; m < N; ++m) {
+            int best = 0;
+            long bestc = -labs((long)m - kp[0]);
+            for (int j = 1; j < n; ++j) {
+                const long c = -labs((long)m - kp[j]);
+                if (c > bestc) { bestc = c; best = j; } /* first maximum: slots ascend with position */
+            }
+            match[m] = best;
+        }
+        double *acc = (double *)malloc(sizeof(double) * (size_t)D);
+        for (int h = 0; h < Hkv; ++h)
+            for (int which = 0; which < 2; ++which) {
+                const float *src = (which ? v : k) + ((size_t)bl * Hkv + h) * (size_t)N * D;
+                float *dst = (which ? vc : kc) + ((size_t)seg_off[bl] * Hkv + (size_t)h * cap) * D;
+                for (int j = 0; j < n; ++j) {
+                    int cnt = 0;
+                    for (int x = 0; x < D; ++x) acc[x] = 0.0;
+                    for (int m = 0; m < N; ++m)
+                        if (match[m] == j) {
+                            ++cnt;
+                            for (int x = 0; x < D; ++x) acc[x] += (double)src[(size_t)m * D + x];
+                        }
+                    for (int x = 0; x < D; ++x) {
+                        const double mean = acc[x] / (double)cnt;
+                        dst[(size_t)j * D + x] = storage_bf16 ? pkvo_round_bf16(mean) : (float)mean;
+                    }
+                }
+            }
+        free(acc);
+        free(match);
+    }
+}

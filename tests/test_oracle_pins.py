@@ -622,3 +622,81 @@ def test_evict_refuses_bad_capacity_or_distance():
         run_evict(72, [8], 8, 2, 6, extra=1)        # survivors do not fit in front of the ring
     x = run_evict(73, [3], 8, 2, 6, extra=0)        # R small enough that nothing survives in 6 steps
     assert x["states"][-1][0][0] == 3
+
+
+# --------------------------------------------------------------- Gini diagnostic and cache merging
+def test_gini_matches_mean_absolute_difference_and_closed_forms():
+    """G = sum_ij |x_i - x_j| / (2 N sum x) relates to the Lorenz-curve (trapezoid) form by the factor the
+    discrete curve carries: G_lorenz = G_mad exactly for the same weights; flat -> 0, one-hot -> (N-1)/N,
+    geometric weights have a closed form."""
+    from fractions import Fraction
+    r = np.random.default_rng(5)
+    imp = (r.random((2, 3, 37)) ** 3).astype(np.float32) + 1e-3
+    imp[0, 0] = 1.0                       # flat
+    imp[0, 1] = 0.0; imp[0, 1, 11] = 2.0  # one-hot
+    sel = oracle.rank(imp)
+    got = oracle.gini(sel["cum"])
+    N = imp.shape[-1]
+    for b in range(2):
+        for l in range(3):
+            w = [int(np.floor(np.float64(x) * 2.0 ** 36)) for x in imp[b, l]]
+            tot = sum(w)
+            mad = Fraction(sum(abs(a - c) for a in w for c in w), 2 * N * tot)
+            assert abs(got[b, l] - float(mad)) < 1e-12
+    assert got[0, 0] == 0.0
+    assert abs(got[0, 1] - (N - 1) / N) < 1e-15
+    # weights 2^-i (exact in fp32 and in the fixed point): sum_k C_k and T in closed form
+    n = 20
+    geo = (2.0 ** -np.arange(n)).astype(np.float32)[None, None]
+    g = oracle.gini(oracle.rank(geo)["cum"])[0, 0]
+    T = 2 - 2.0 ** (1 - n)
+    S = sum(2 - 2.0 ** (1 - k) for k in range(1, n + 1))
+    assert abs(g - (2 * S / T - n - 1) / n) < 1e-14
+    # a more concentrated layer has the larger coefficient and, under one shared p, the shorter prefix
+    conc = np.stack([np.sort(r.random(64).astype(np.float32) ** 8 + 1e-4)[::-1],
+                     np.sort(r.random(64).astype(np.float32) + 0.5)[::-1]])[None]
+    s2 = oracle.select(conc, 40)
+    g2 = oracle.gini(s2["cum"])[0]
+    assert g2[0] > g2[1] and s2["lengths"][0, 0] < s2["lengths"][0, 1]
+
+
+def test_merge_position_is_nearest_kept_average():
+    """Brute force in NumPy: match = argmax of -|m - n| over the kept positions (first maximum = lower
+    position on a tie), merged vector = mean of the group; the groups partition all positions, so the
+    count-weighted sum of the merged vectors equals the sum of all vectors; a full budget changes nothing."""
+    k, v, sel, cache = make_cache_case(91, B=2, L=3, Hkv=2, N=23, D=8, cap=2, frac=0.3)
+    before = {n: cache[n].copy() for n in ("kc", "vc")}
+    oracle.merge_position(cache, k, v)
+    B, L, Hkv, N, D = k.shape
+    for b in range(B):
+        for l in range(L):
+            n = int(sel["lengths"][b, l])
+            kp = oracle.segment(cache, "kept_pos", b, l)[:n]
+            c = -np.abs(np.arange(N)[:, None] - kp[None, :])
+            match = c.argmax(1)                                   # first maximum
+            counts = np.bincount(match, minlength=n)
+            assert counts.sum() == N and (counts >= 1).all() and (match[kp] == np.arange(n)).all()
+            for name, src in (("kc", k), ("vc", v)):
+                seg = oracle.segment(cache, name, b, l)
+                for j in range(n):
+                    want = src[b, l][:, match == j].astype(np.float64).mean(1)
+                    np.testing.assert_allclose(seg[:, j], want, rtol=1e-6, atol=1e-7)
+                mass = (seg[:, :n].astype(np.float64) * counts[None, :, None]).sum(1)
+                np.testing.assert_allclose(mass, src[b, l].astype(np.float64).sum(1), rtol=1e-5, atol=1e-5)
+                assert np.isnan(seg[:, n:]).all()                  # the decode slots stay untouched
+    # tie: position 2 between kept 1 and 3 goes to 1
+    k1 = np.arange(5, dtype=np.float32).reshape(1, 1, 1, 5, 1)
+    order = np.array([[[1, 3, 0, 2, 4]]], np.int32)
+    c1 = oracle.compact(k1, k1, order, np.array([[2]], np.int32), 0)
+    oracle.merge_position(c1, k1, k1)
+    np.testing.assert_array_equal(oracle.segment(c1, "kc", 0, 0)[0, :, 0], [1.0, 3.5])   # {0,1,2} and {3,4}
+    # full budget: every group is a single position
+    kf, vf, self_, cf = make_cache_case(92, frac=1.0, cap=0)
+    ref = cf["kc"].copy()
+    oracle.merge_position(cf, kf, vf)
+    np.testing.assert_array_equal(cf["kc"], ref)
+    # bf16 storage: merged vectors are representable in bfloat16
+    kb, vb, selb, cb = make_cache_case(93, frac=0.4)
+    oracle.merge_position(cb, kb, vb, storage_bf16=True)
+    kc = cb["kc"][~np.isnan(cb["kc"])]
+    assert ((kc.view(np.uint32) & 0xffff) == 0).all()
