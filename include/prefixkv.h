@@ -163,6 +163,29 @@ int prefixkv_compact(const pkv_shape *shape, const void *k, pkv_strides ks, cons
                      int32_t *kept_pos, int32_t *lens, void *ws, size_t ws_bytes,
                      pkv_stream stream);
 
+/* ---- Cache merging by positional distance (Sec. 4.3, "Eviction or merging": the pruned vector at
+ * position m is matched to the retained position n with the largest metric c = -|m - n| and every
+ * retained vector becomes the average of itself and the pruned vectors matched to it; the variant the
+ * paper calls "Position".  The paper reports it as neutral to slightly harmful, so it is optional).
+ * Runs in place on the output of prefixkv_compact, before the first decode step: slot j of segment
+ * (b,l) holds position kept_pos[j]; a pruned position half way between two kept ones goes to the lower
+ * (first maximum of the metric); keys and values of all KV heads are averaged alike, fp32 sums in
+ * ascending position, one rounding to the storage dtype.  Only the first lens[b,l] slots are written.
+ *   k, v [dev]: the uncompressed tensors given to prefixkv_compact;  everything else as produced by it.
+ * The feature-similarity variant ("Feature") is not provided. */
+int prefixkv_merge_position(const pkv_shape *shape, const void *k, pkv_strides ks, const void *v,
+                            pkv_strides vs, const int64_t *seg_off, const int32_t *caps,
+                            const int32_t *kept_pos, const int32_t *lens, void *kc, void *vc,
+                            pkv_stream stream);
+
+/* ---- Diagnostic: Gini coefficient of every layer's priority sequence (Sec. 4.3, "Relation between KV
+ * cache size and importance distribution": layers with a more concentrated distribution, i.e. a higher
+ * coefficient, receive smaller caches).  From the exact cumulative sums of prefixkv_select / _rank:
+ *   gini[b,l] = (2 * (C_1 + ... + C_N) / C_N - N - 1) / N   (Lorenz curve, trapezoid rule);
+ * 0 for a flat layer, (N-1)/N when one position holds everything, 0 when C_N = 0.
+ *   cum [dev] u64 [B,L,N];  gini [dev] f64 [B,L]. */
+int prefixkv_gini(int B, int L, int N, const uint64_t *cum, double *gini, pkv_stream stream);
+
 /* Tokens to allocate for kc/vc/kept_pos when every sequence keeps at most `budget_tokens`. */
 int64_t prefixkv_cache_tokens_upper_bound(int B, int64_t budget_tokens, int L, int decode_capacity);
 

@@ -73,6 +73,10 @@ def load(path: Optional[str] = None) -> C.CDLL:
     L.prefixkv_rank.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     L.prefixkv_offline_config.restype = C.c_int
     L.prefixkv_offline_config.argtypes = [i32, i32, i32, vp, i64, i32, vp, vp]
+    L.prefixkv_gini.restype = C.c_int
+    L.prefixkv_gini.argtypes = [i32, i32, i32, vp, vp, vp]
+    L.prefixkv_merge_position.restype = C.c_int
+    L.prefixkv_merge_position.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, vp, vp, vp, vp, vp]
     L.prefixkv_compact.restype = C.c_int
     L.prefixkv_compact.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, i32, vp, vp, vp,
                                    vp, vp, vp, vp, sz, vp]
@@ -306,6 +310,35 @@ def prefixkv_compact(k: torch.Tensor, v: torch.Tensor, order: torch.Tensor, leng
                                  _stream())
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_compact")
+    return out
+
+
+def prefixkv_merge_position(cache: CompactResult, k: torch.Tensor, v: torch.Tensor) -> CompactResult:
+    """Average every pruned position into the nearest kept one, in place on a freshly compacted cache."""
+    _need_cuda(k, v)
+    B, L, Hkv, N, D = k.shape
+    if v.shape != k.shape or v.dtype != k.dtype or k.dtype != cache.kc.dtype or D != cache.D or Hkv != cache.Hkv:
+        raise ValueError("k, v must be the [B,L,Hkv,N,D] tensors the cache was compacted from")
+    s = _shape(B, L, Hkv, Hkv, N, D, _dtype_code(k))
+    rc = load().prefixkv_merge_position(C.byref(s), _ptr(k), _strides5(k), _ptr(v), _strides5(v),
+                                        _ptr(cache.seg_off), _ptr(cache.caps), _ptr(cache.kept_pos),
+                                        _ptr(cache.lens), _ptr(cache.kc), _ptr(cache.vc), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_merge_position")
+    return cache
+
+
+def prefixkv_gini(cum: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """cum [B,L,N] (i64 holding the u64 sums of prefixkv_select / prefixkv_rank) -> Gini coefficients [B,L] f64."""
+    _need_cuda(cum, out)
+    if cum.dtype != torch.int64 or cum.dim() != 3 or not cum.is_contiguous():
+        raise ValueError("cum must be contiguous i64 [B,L,N]")
+    B, L, N = cum.shape
+    if out is None:
+        out = torch.empty((B, L), dtype=torch.float64, device=cum.device)
+    rc = load().prefixkv_gini(B, L, N, _ptr(cum), _ptr(out), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_gini")
     return out
 
 

@@ -126,6 +126,29 @@ int prefixkv_compact(const pkv_shape* s, const void* k, pkv_strides ks, const vo
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
 
+int prefixkv_gini(int B, int L, int N, const uint64_t* cum, double* gini, pkv_stream stream) {
+    if (!cum || !gini) return PKV_ERR_NULL;
+    if (B < 1 || L < 1 || L > kMaxL || N < 1 || N > kMaxN) return PKV_ERR_DIM;
+    const hipError_t e = launch_gini(B, L, N, cum, gini, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int prefixkv_merge_position(const pkv_shape* s, const void* k, pkv_strides ks, const void* v, pkv_strides vs,
+                            const int64_t* seg_off, const int32_t* caps, const int32_t* kept_pos,
+                            const int32_t* lens, void* kc, void* vc, pkv_stream stream) {
+    if (!s || !k || !v || !seg_off || !caps || !kept_pos || !lens || !kc || !vc) return PKV_ERR_NULL;
+    if (!shape_ok(s)) return PKV_ERR_DIM;
+    if (!dtype_ok(s)) return PKV_ERR_DTYPE;
+    const int esize = s->dtype == PKV_F32 ? 4 : 2;
+    if (!strides_ok(ks, esize) || !strides_ok(vs, esize) || !aligned16(k) || !aligned16(v) ||
+        !aligned16(kc) || !aligned16(vc))
+        return PKV_ERR_STRIDE;
+    if ((size_t)8 * s->Hkv * s->B * s->L > 0x7fffffffull) return PKV_ERR_UNSUPPORTED;
+    const hipError_t e = launch_merge_position(*s, k, to_strides(ks), v, to_strides(vs), seg_off, caps, kept_pos,
+                                               lens, kc, vc, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
 int64_t prefixkv_cache_tokens_upper_bound(int B, int64_t budget_tokens, int L, int decode_capacity) {
     if (B < 1 || L < 1 || budget_tokens < 0 || decode_capacity < 0) return 0;
     return (int64_t)B * (budget_tokens + (int64_t)L * decode_capacity);

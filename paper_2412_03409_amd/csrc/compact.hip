@@ -119,7 +119,118 @@ compact_gather_kernel(int nchunk, int Hkv, int L, int row_bytes, const unsigned 
     }
 }
 
+// Cache merging by positional distance (Sec. 4.3, "Eviction or merging", metric -|m - n|): every pruned
+// position is averaged into the nearest kept one (half way: the lower), keys and values of all heads
+// alike.  The kept positions ascend along the slots, so the positions matched to slot j are the contiguous
+// range (mid(j-1), mid(j)] with mid(j) = floor((kept_pos[j] + kept_pos[j+1]) / 2): no matching pass is
+// needed.  One workgroup per (segment, kv head, part of the slot list); a wavefront takes every 4th slot of
+// the part and walks its range with 64/LPR rows per load instruction, two instructions deep; the row
+// groups' fp32 sums are added in a fixed order.  Every row of K and V is read exactly once per launch.
+template <int LPR, bool BF16>
+__global__ void __launch_bounds__(256)
+merge_position_kernel(int nparts, int Hkv, int L, int N, int row_bytes, const unsigned char* __restrict__ k,
+                      Strides ks, const unsigned char* __restrict__ v, Strides vs, int esize,
+                      const int64_t* __restrict__ seg_off, const int32_t* __restrict__ caps,
+                      const int32_t* __restrict__ lens, const int32_t* __restrict__ kept_pos,
+                      unsigned char* __restrict__ kc, unsigned char* __restrict__ vc) {
+    constexpr int RPI = kWave / LPR;         // rows per wavefront-wide load
+    constexpr int EPL = BF16 ? 8 : 4;        // elements per lane
+    const int part = blockIdx.x % nparts;
+    const int h = (blockIdx.x / nparts) % Hkv, seg = blockIdx.x / (nparts * Hkv);
+    const int len = lens[seg];
+    const int per = (len + nparts - 1) / nparts;
+    const int j0 = part * per, j1 = min(len, j0 + per);
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    const int sub = lane % LPR, rg = lane / LPR;
+    const int b = seg / L, l = seg % L;
+    const int64_t off = seg_off[seg];
+    const int cap = caps[seg];
+    const int32_t* kp = kept_pos + off;
+    const unsigned char* kb = k + (ks.b * b + ks.l * l + ks.h * h) * (int64_t)esize + sub * 16;
+    const unsigned char* vb = v + (vs.b * b + vs.l * l + vs.h * h) * (int64_t)esize + sub * 16;
+    const int64_t kstep = ks.n * (int64_t)esize, vstep = vs.n * (int64_t)esize;
+    for (int j = j0 + wv; j < j1; j += 4) {
+        const int pj = kp[j];
+        const int lo = j == 0 ? 0 : (kp[j - 1] + pj) / 2 + 1;
+        const int hi = j == len - 1 ? N : (pj + kp[j + 1]) / 2 + 1;
+        float ka[EPL], va[EPL];
+#pragma unroll
+        for (int x = 0; x < EPL; ++x) { ka[x] = 0.f; va[x] = 0.f; }
+        for (int m0 = lo; m0 < hi; m0 += 2 * RPI) {
+            const int ma = m0 + rg, mb = m0 + RPI + rg;
+            uint4 r[4];
+            r[0] = r[1] = r[2] = r[3] = make_uint4(0, 0, 0, 0);   // zero bits are 0.0 in both formats
+            if (ma < hi) { r[0] = *(const uint4*)(kb + kstep * ma); r[1] = *(const uint4*)(vb + vstep * ma); }
+            if (mb < hi) { r[2] = *(const uint4*)(kb + kstep * mb); r[3] = *(const uint4*)(vb + vstep * mb); }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint32_t w[4] = {r[t].x, r[t].y, r[t].z, r[t].w};
+                float* acc = (t & 1) ? va : ka;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    if constexpr (BF16) {
+                        acc[2 * x] += __uint_as_float(w[x] << 16);
+                        acc[2 * x + 1] += __uint_as_float(w[x] & 0xffff0000u);
+                    } else {
+                        acc[x] += __uint_as_float(w[x]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int sh = LPR; sh < kWave; sh <<= 1)
+#pragma unroll
+            for (int x = 0; x < EPL; ++x) {
+                ka[x] += __shfl_xor(ka[x], sh, kWave);
+                va[x] += __shfl_xor(va[x], sh, kWave);
+            }
+        if (rg == 0) {
+            const float cnt = (float)(hi - lo);      // >= 1: the range holds the kept position itself
+            const int64_t dst = (off * Hkv + (int64_t)h * cap + j) * row_bytes + sub * 16;
+            if constexpr (BF16) {
+                uint32_t ko[4], vo[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    ko[x] = (uint32_t)f32_to_bf16(ka[2 * x] / cnt) | ((uint32_t)f32_to_bf16(ka[2 * x + 1] / cnt) << 16);
+                    vo[x] = (uint32_t)f32_to_bf16(va[2 * x] / cnt) | ((uint32_t)f32_to_bf16(va[2 * x + 1] / cnt) << 16);
+                }
+                *(uint4*)(kc + dst) = make_uint4(ko[0], ko[1], ko[2], ko[3]);
+                *(uint4*)(vc + dst) = make_uint4(vo[0], vo[1], vo[2], vo[3]);
+            } else {
+                *(uint4*)(kc + dst) = make_uint4(__float_as_uint(ka[0] / cnt), __float_as_uint(ka[1] / cnt),
+                                                 __float_as_uint(ka[2] / cnt), __float_as_uint(ka[3] / cnt));
+                *(uint4*)(vc + dst) = make_uint4(__float_as_uint(va[0] / cnt), __float_as_uint(va[1] / cnt),
+                                                 __float_as_uint(va[2] / cnt), __float_as_uint(va[3] / cnt));
+            }
+        }
+    }
+}
+
 size_t compact_ws_bytes(const pkv_shape&) { return 0; }
+
+hipError_t launch_merge_position(const pkv_shape& s, const void* k, Strides ks, const void* v, Strides vs,
+                                 const int64_t* seg_off, const int32_t* caps, const int32_t* kept_pos,
+                                 const int32_t* lens, void* kc, void* vc, hipStream_t st) {
+    const int nseg = s.B * s.L;
+    const bool bf16 = s.dtype == PKV_BF16;
+    const int esize = bf16 ? 2 : 4;
+    const int row_bytes = s.D * esize;
+    const int lpr = row_bytes / 16;
+    // enough workgroups to fill the chip a few times over, but never tiny ones
+    int nparts = (4096 + nseg * s.Hkv - 1) / (nseg * s.Hkv);
+    nparts = nparts < 1 ? 1 : (nparts > 8 ? 8 : nparts);
+    dim3 grid((uint32_t)((size_t)nparts * s.Hkv * nseg));
+#define PKV_MERGE(LPR, BF)                                                                                   \
+    hipLaunchKernelGGL((merge_position_kernel<LPR, BF>), grid, dim3(256), 0, st, nparts, s.Hkv, s.L, s.N,     \
+                       row_bytes, (const unsigned char*)k, ks, (const unsigned char*)v, vs, esize, seg_off,  \
+                       caps, lens, kept_pos, (unsigned char*)kc, (unsigned char*)vc)
+    if (bf16 && lpr == 8) PKV_MERGE(8, true);
+    else if (bf16) PKV_MERGE(16, true);
+    else if (lpr == 16) PKV_MERGE(16, false);
+    else PKV_MERGE(32, false);
+#undef PKV_MERGE
+    return hipGetLastError();
+}
 
 hipError_t launch_compact(const pkv_shape& s, const void* k, Strides ks, const void* v, Strides vs,
                           const int32_t* order, const int32_t* lengths, int decode_capacity,

@@ -51,6 +51,11 @@ hipError_t launch_rank(int B, int L, int N, const float* importance, int32_t* or
 hipError_t launch_offline_config(int S, int L, int N, const int32_t* sample_lengths, int64_t budget,
                                  int copies, int32_t* lengths, hipStream_t st);
 
+hipError_t launch_gini(int B, int L, int N, const uint64_t* cum, double* gini, hipStream_t st);
+hipError_t launch_merge_position(const pkv_shape& s, const void* k, Strides ks, const void* v, Strides vs,
+                                 const int64_t* seg_off, const int32_t* caps, const int32_t* kept_pos,
+                                 const int32_t* lens, void* kc, void* vc, hipStream_t st);
+
 size_t compact_ws_bytes(const pkv_shape& s);
 hipError_t launch_compact(const pkv_shape& s, const void* k, Strides ks, const void* v, Strides vs,
                           const int32_t* order, const int32_t* lengths, int decode_capacity,

@@ -293,6 +293,34 @@ status_reduce_kernel(int L, const int32_t* __restrict__ seg_status, int32_t* __r
     if (lane == 0) status[b] = st;
 }
 
+// Gini coefficient of every layer's priority sequence (Sec. 4.3): G = (2 * sum_k C_k / C_N - N - 1) / N on the
+// exact cumulative sums.  sum_k C_k can reach 2^66, so it is kept as a (high, low) pair of 64-bit words; the
+// per-thread pairs are added up in thread order by one thread.
+__global__ void __launch_bounds__(256)
+gini_kernel(int N, const uint64_t* __restrict__ cum, double* __restrict__ gini) {
+    __shared__ uint64_t s_lo[256], s_hi[256];
+    const uint64_t* c = cum + (size_t)blockIdx.x * N;
+    uint64_t lo = 0, hi = 0;
+    for (int i = threadIdx.x; i < N; i += 256) {
+        const uint64_t a = c[i], t = lo + a;
+        hi += t < lo ? 1 : 0;
+        lo = t;
+    }
+    s_lo[threadIdx.x] = lo; s_hi[threadIdx.x] = hi;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        lo = 0; hi = 0;
+        for (int i = 0; i < 256; ++i) {
+            const uint64_t t = lo + s_lo[i];
+            hi += s_hi[i] + (t < lo ? 1 : 0);
+            lo = t;
+        }
+        const double S = (double)hi * 18446744073709551616.0 + (double)lo;
+        const double T = (double)c[N - 1];
+        gini[blockIdx.x] = T > 0.0 ? (2.0 * (S / T) - (double)N - 1.0) / (double)N : 0.0;
+    }
+}
+
 static int pow2_at_least(int n) { int p = 64; while (p < n) p <<= 1; return p; }
 
 size_t select_ws_bytes(int B, int L, int N) { (void)N; return (size_t)B * L * sizeof(int32_t); }
@@ -346,6 +374,11 @@ hipError_t launch_offline_config(int S, int L, int N, const int32_t* sample_leng
                                  int copies, int32_t* lengths, hipStream_t st) {
     hipLaunchKernelGGL(offline_config_kernel, dim3(1), dim3(kWave), 0, st, S, L, N, sample_lengths, budget,
                        copies, lengths);
+    return hipGetLastError();
+}
+
+hipError_t launch_gini(int B, int L, int N, const uint64_t* cum, double* gini, hipStream_t st) {
+    hipLaunchKernelGGL(gini_kernel, dim3(B * L), dim3(256), 0, st, N, cum, gini);
     return hipGetLastError();
 }
 

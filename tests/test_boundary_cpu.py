@@ -111,6 +111,23 @@ def test_rank_and_offline_config_argument_errors():
     assert off(budget=0) == 6
 
 
+def test_gini_and_merge_argument_errors():
+    lib = P.load()
+    assert lib.prefixkv_gini(1, 4, 128, None, FAKE, None) == 1
+    assert lib.prefixkv_gini(1, 4, 128, FAKE, None, None) == 1
+    assert lib.prefixkv_gini(1, 65, 128, FAKE, FAKE, None) == 2
+    assert lib.prefixkv_gini(1, 4, 0, FAKE, FAKE, None) == 2
+    st = Bd._Strides(4 * 2 * 128 * 64, 2 * 128 * 64, 128 * 64, 64)
+    mg = lambda k=FAKE, kp=FAKE, sh=_shape(), ks=st: lib.prefixkv_merge_position(
+        C.byref(sh), k, ks, FAKE, st, FAKE, FAKE, kp, FAKE, FAKE, FAKE, None)
+    assert mg(k=None) == 1
+    assert mg(kp=None) == 1
+    assert mg(sh=_shape(D=32)) == 2
+    assert mg(sh=_shape(dtype=7)) == 3
+    assert mg(ks=Bd._Strides(0, 0, 0, 6)) == 4
+    assert mg(k=C.c_void_p(0x1004)) == 4
+
+
 def test_compact_and_decode_argument_errors():
     lib = P.load()
     st = Bd._Strides(4 * 2 * 128 * 64, 2 * 128 * 64, 128 * 64, 64)

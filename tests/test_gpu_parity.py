@@ -296,6 +296,57 @@ def test_compact_with_empty_segments():
     check_cache(got, want, torch.bfloat16)
 
 
+# ------------------------------------------------- Gini diagnostic and position merging (Sec. 4.3)
+@pytest.mark.parametrize("B,L,N", [(1, 1, 1), (2, 4, 128), (3, 32, 680), (1, 3, 8192)])
+def test_gini_matches_oracle(B, L, N):
+    imp = synthetic_importance(B, L, N, seed=31 + N)
+    if N > 1:
+        imp[0, 0] = 1.0                               # flat layer
+        imp[0, L - 1] = 0.0; imp[0, L - 1, N // 2] = 3.0   # everything on one position
+    rk = P.prefixkv_rank(imp.to(DEV))
+    got = P.prefixkv_gini(rk.cum).cpu().numpy()
+    want = oracle.gini(oracle.rank(imp.numpy())["cum"])
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-15)
+    if N > 1 and L > 1:
+        assert got[0, 0] == 0.0 and abs(got[0, L - 1] - (N - 1) / N) < 1e-14
+
+
+@pytest.mark.parametrize("B,L,Hkv,N,D,dtype,frac", [
+    (1, 4, 2, 128, 64, torch.float32, 0.5),
+    (2, 3, 4, 333, 128, torch.bfloat16, 0.2),
+    (2, 2, 2, 70, 64, torch.bfloat16, 0.33),
+    (1, 2, 2, 100, 128, torch.float32, 1.0),          # full budget: nothing to merge
+    (1, 2, 2, 97, 128, torch.bfloat16, 0.03),         # one or two kept positions take everything
+    (1, 3, 1, 8192, 128, torch.bfloat16, 0.1),
+])
+def test_merge_position_matches_oracle(B, L, Hkv, N, D, dtype, frac):
+    g = torch.Generator().manual_seed(N + D + 1)
+    k = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+    v = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+    imp = synthetic_importance(B, L, N, seed=N + 5)
+    budget = max(L + 1, int(frac * L * N))
+    sel = oracle.select(imp.numpy(), budget)
+    got, want = run_compact(k, v, sel, 3, budget)
+    P.prefixkv_merge_position(got, k.to(DEV), v.to(DEV))
+    bf = dtype == torch.bfloat16
+    oracle.merge_position(want, np32(k), np32(v), storage_bf16=bf)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(got.lens.cpu().numpy(), want["lens"])
+    kc, vc = np32(got.kc), np32(got.vc)
+    # fp32 sums on the GPU, fp64 in the oracle: equal up to one unit in the last place of the storage dtype
+    rtol = 2.0 ** -7 if bf else 2e-6
+    for b in range(B):
+        for l in range(L):
+            off, cap, n = int(want["seg_off"][b, l]), int(want["caps"][b, l]), int(want["lens"][b, l])
+            gk = kc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
+            gv = vc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
+            np.testing.assert_allclose(gk, oracle.segment(want, "kc", b, l)[:, :n], rtol=rtol, atol=1e-6)
+            np.testing.assert_allclose(gv, oracle.segment(want, "vc", b, l)[:, :n], rtol=rtol, atol=1e-6)
+    if frac == 1.0:   # every group is one position: bit-identical to the plain gather
+        plain, pw = run_compact(k, v, sel, 3, budget)
+        check_cache(got, pw, dtype)
+
+
 # --------------------------------------------------------------------------------------- decode
 def run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed, layer_range=None, zero_seq=False):
     g = torch.Generator().manual_seed(seed)
