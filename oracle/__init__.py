@@ -72,6 +72,19 @@ def importance(q, k, scale, want_lse: bool = False, m_lo: int = 0):
     return (imp, lse) if want_lse else imp
 
 
+def prefill_attn(q, k, v, scale, out_bf16: bool = False):
+    """Causal attention of the whole prompt: q [B,L,H,N,D], k/v [B,L,Hkv,N,D], scale [L]
+    -> (out [B,L,H,N,D] f32, lse [B,L,H,N] f64)."""
+    q, k, v, scale = _f32(q), _f32(k), _f32(v), _f32(scale)
+    B, L, H, N, D = q.shape
+    Hkv = k.shape[2]
+    assert k.shape == (B, L, Hkv, N, D) and v.shape == k.shape and H % Hkv == 0 and scale.shape == (L,)
+    out = np.empty((B, L, H, N, D), dtype=np.float32)
+    lse = np.empty((B, L, H, N), dtype=np.float64)
+    lib().pkvo_prefill_attn(B, L, H, Hkv, N, D, _p(q), _p(k), _p(v), _p(scale), _p(out), _p(lse), int(out_bf16))
+    return out, lse
+
+
 def sort_prefix_layer(imp):
     """One layer: importance [N] -> (status, order [N] i32, cum [N] u64, prefix [N] f32)."""
     imp = _f32(imp)

@@ -590,3 +590,48 @@ void pkvo_merge_position(int B, int L, int Hkv, int N, int D, const float *k, co
         free(match);
     }
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * Causal prefill attention of one prompt (Sec. 3.1: the prefill phase computes the attention of all
+ * prompt tokens; Sec. 3.2 builds the importance from the same score matrix a_l^{i,m,n}).
+ *   out[m] = sum_{n<=m} a[m][n] * v[n],  a[m][n] = exp(scale*q_m.k_n) / sum_{j<=m} exp(scale*q_m.k_j)
+ *   lse[m] = log sum_{j<=m} exp(scale*q_m.k_j)      (what the importance stage accepts from its caller)
+ * q [B,L,H,N,D], k/v [B,L,Hkv,N,D] -> out [B,L,H,N,D] (rounded to bf16 if out_bf16), lse [B,L,H,N] f64.
+ * ------------------------------------------------------------------------------------------- */
+void pkvo_prefill_attn(int B, int L, int H, int Hkv, int N, int D, const float *q, const float *k,
+                       const float *v, const float *scale, float *out, double *lse, int out_bf16) {
+    const int grp = H / Hkv;
+    const long units = (long)B * L * H;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)N);
+#pragma omp for schedule(dynamic, 1)
+        for (long u = 0; u < units; ++u) {
+            const int h = (int)(u % H);
+            const int l = (int)((u / H) % L);
+            const long bl = u / H;
+            const float *qh = q + (size_t)u * N * D;
+            const float *kh = k + ((size_t)bl * Hkv + h / grp) * (size_t)N * D;
+            const float *vh = v + ((size_t)bl * Hkv + h / grp) * (size_t)N * D;
+            for (int m = 0; m < N; ++m) {
+                double mx = -INFINITY;
+                for (int n = 0; n <= m; ++n) {
+                    double dot = 0.0;
+                    for (int d = 0; d < D; ++d) dot += (double)qh[(size_t)m * D + d] * (double)kh[(size_t)n * D + d];
+                    s[n] = (double)scale[l] * dot;
+                    if (s[n] > mx) mx = s[n];
+                }
+                double den = 0.0;
+                for (int n = 0; n <= m; ++n) { s[n] = exp(s[n] - mx); den += s[n]; }
+                lse[(size_t)u * N + m] = mx + log(den);
+                for (int d = 0; d < D; ++d) {
+                    double acc = 0.0;
+                    for (int n = 0; n <= m; ++n) acc += s[n] * (double)vh[(size_t)n * D + d];
+                    acc /= den;
+                    out[((size_t)u * N + m) * D + d] = out_bf16 ? pkvo_round_bf16(acc) : (float)acc;
+                }
+            }
+        }
+        free(s);
+    }
+}

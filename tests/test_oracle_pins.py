@@ -700,3 +700,34 @@ def test_merge_position_is_nearest_kept_average():
     oracle.merge_position(cb, kb, vb, storage_bf16=True)
     kc = cb["kc"][~np.isnan(cb["kc"])]
     assert ((kc.view(np.uint32) & 0xffff) == 0).all()
+
+
+# ------------------------------------------------------------------ causal prefill attention
+def test_prefill_attention_matches_dense_numpy_and_ties_to_importance():
+    """Dense masked softmax in NumPy (incl. GQA and per-layer scale); constant V gives that constant; with
+    V = identity the output rows are the attention probabilities, whose column sums, averaged over the
+    heads, are the importance of Sec. 3.2; lse agrees with the importance oracle's; row 0 returns v_0."""
+    q, k, sc = rng_qk(71, 2, 2, 4, 2, 13, 8)
+    r = np.random.default_rng(72)
+    v = r.standard_normal(k.shape).astype(np.float32)
+    out, lse = oracle.prefill_attn(q, k, v, sc)
+    B, L, H, N, D = q.shape
+    kk, vv = np.repeat(k, 2, axis=2).astype(np.float64), np.repeat(v, 2, axis=2).astype(np.float64)
+    s = np.einsum("blhmd,blhnd->blhmn", q.astype(np.float64), kk) * sc.astype(np.float64)[None, :, None, None, None]
+    s = np.where(np.tril(np.ones((N, N), dtype=bool)), s, -np.inf)
+    mx = s.max(-1, keepdims=True)
+    e = np.exp(s - mx)
+    a = e / e.sum(-1, keepdims=True)
+    np.testing.assert_allclose(out, np.einsum("blhmn,blhnd->blhmd", a, vv), rtol=1e-5, atol=1e-6)
+    np.testing.assert_allclose(lse, (mx + np.log(e.sum(-1, keepdims=True)))[..., 0], rtol=1e-12, atol=1e-12)
+    np.testing.assert_array_equal(out[..., 0, :], np.repeat(v, 2, axis=2)[..., 0, :])       # row 0 sees only key 0
+    _, lse_imp = oracle.importance(q, k, sc, want_lse=True)
+    np.testing.assert_allclose(lse, lse_imp, rtol=1e-13, atol=1e-13)
+    const, _ = oracle.prefill_attn(q, k, np.full_like(v, 0.75), sc)
+    np.testing.assert_allclose(const, 0.75, rtol=1e-6)
+    # V = identity (D = N): out[m, n] = a[m][n]
+    q2, k2, sc2 = rng_qk(73, 1, 2, 2, 2, 8, 8)
+    eye = np.broadcast_to(np.eye(8, dtype=np.float32), (1, 2, 2, 8, 8)).copy()
+    probs, _ = oracle.prefill_attn(q2, k2, eye, sc2)
+    assert (np.triu(probs[0, 0, 0], 1) == 0).all()                                          # causal
+    np.testing.assert_allclose(probs.sum(-2).mean(2), oracle.importance(q2, k2, sc2), rtol=1e-6)
