@@ -86,6 +86,20 @@ int prefixkv_importance(const pkv_shape *shape, const void *q, pkv_strides qs, c
                         pkv_strides ks, const float *scale, const float *lse, float *importance,
                         void *ws, size_t ws_bytes, pkv_stream stream);
 
+/* ---- The step before the path: causal prefill attention that hands its row log-sum-exp to stage 1
+ * (Sec. 3.1: the prefill phase attends over the whole prompt; Sec. 3.2 defines the importance on the
+ * same score matrix, so a prefill kernel that keeps lse saves stage 1 one of its two passes).
+ *   out[b,l,h,m,:] = sum_{n<=m} softmax_{j<=m}(scale[l] * q_m.k_j)[n] * v[b,l,g(h),n,:]
+ *   lse[b,l,h,m]   = log sum_{j<=m} exp(scale[l] * q_m.k_j)         (natural log, fp32)
+ * bf16 storage only (PKV_ERR_UNSUPPORTED otherwise); both products on bf16 MFMA with fp32 accumulation,
+ * probabilities rounded to bf16 for the second product, fp32 softmax.
+ *   q [dev] [B,L,H,N,D] strides qs;  k, v [dev] [B,L,Hkv,N,D] strides ks, vs;  scale [dev] fp32 [L]
+ *   out [dev] bf16 [B,L,H,N,D] dense;  lse [dev] fp32 [B,L,H,N] dense: pass it as `lse` to
+ *   prefixkv_importance.  No workspace. */
+int prefixkv_prefill_attn(const pkv_shape *shape, const void *q, pkv_strides qs, const void *k,
+                          pkv_strides ks, const void *v, pkv_strides vs, const float *scale,
+                          void *out, float *lse, pkv_stream stream);
+
 /* ---- Stages 2+3: priority sequences, cumulative priority and the global search (Sec. 3.2 for
  * the normalised, sorted, cumulated importance P_l^o; Sec. 3.3, Eq. 1 and Algorithm 1 for p).
  * Per sequence b and layer l:

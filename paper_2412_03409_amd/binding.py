@@ -66,6 +66,8 @@ def load(path: Optional[str] = None) -> C.CDLL:
     L.prefixkv_workspace_bytes.argtypes = [i32, C.POINTER(_Shape), i32]
     L.prefixkv_importance.restype = C.c_int
     L.prefixkv_importance.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, vp, vp, sz, vp]
+    L.prefixkv_prefill_attn.restype = C.c_int
+    L.prefixkv_prefill_attn.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, _Strides, vp, vp, vp, vp]
     L.prefixkv_select.restype = C.c_int
     L.prefixkv_select.argtypes = [i32, i32, i32, vp, C.POINTER(_SelectParams), vp, vp, vp, vp, vp, vp, vp,
                                   vp, vp, sz, vp]
@@ -175,6 +177,29 @@ def prefixkv_importance(q: torch.Tensor, k: torch.Tensor, scale: torch.Tensor,
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_importance")
     return out
+
+
+def prefixkv_prefill_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scale: torch.Tensor,
+                          out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None):
+    """Causal attention over the prompt: q [B,L,H,N,D], k/v [B,L,Hkv,N,D] (bf16), scale [L] f32
+    -> (out [B,L,H,N,D] bf16, lse [B,L,H,N] f32, ready to be passed to prefixkv_importance)."""
+    _need_cuda(q, k, v, scale, out, lse)
+    B, L, H, N, D = q.shape
+    Hkv = k.shape[2]
+    if k.shape != (B, L, Hkv, N, D) or v.shape != k.shape or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("k, v must be [B,L,Hkv,N,D] with q's dtype")
+    if scale.dtype != torch.float32 or scale.shape != (L,) or not scale.is_contiguous():
+        raise ValueError("scale must be contiguous f32 [L]")
+    if out is None:
+        out = torch.empty((B, L, H, N, D), dtype=q.dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, L, H, N), dtype=torch.float32, device=q.device)
+    s = _shape(B, L, H, Hkv, N, D, _dtype_code(q))
+    rc = load().prefixkv_prefill_attn(C.byref(s), _ptr(q), _strides5(q), _ptr(k), _strides5(k), _ptr(v),
+                                      _strides5(v), _ptr(scale), _ptr(out), _ptr(lse), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_prefill_attn")
+    return out, lse
 
 
 @dataclass

@@ -73,6 +73,22 @@ int prefixkv_importance(const pkv_shape* s, const void* q, pkv_strides qs, const
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
 
+int prefixkv_prefill_attn(const pkv_shape* s, const void* q, pkv_strides qs, const void* k, pkv_strides ks,
+                          const void* v, pkv_strides vs, const float* scale, void* out, float* lse,
+                          pkv_stream stream) {
+    if (!s || !q || !k || !v || !scale || !out || !lse) return PKV_ERR_NULL;
+    if (!shape_ok(s)) return PKV_ERR_DIM;
+    if (!dtype_ok(s)) return PKV_ERR_DTYPE;
+    if (s->dtype != PKV_BF16) return PKV_ERR_UNSUPPORTED;
+    if (!strides_ok(qs, 2) || !strides_ok(ks, 2) || !strides_ok(vs, 2) || !aligned16(q) || !aligned16(k) ||
+        !aligned16(v) || !aligned16(out))
+        return PKV_ERR_STRIDE;
+    if ((size_t)s->B * s->L * s->H * ((s->N + 127) / 128) > 0x7fffffffull) return PKV_ERR_UNSUPPORTED;
+    const hipError_t e = launch_prefill_attn(*s, q, to_strides(qs), k, to_strides(ks), v, to_strides(vs), scale, out,
+                                             lse, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
 int prefixkv_select(int B, int L, int N, const float* importance, const pkv_select_params* params,
                     int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
                     int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, size_t ws_bytes,

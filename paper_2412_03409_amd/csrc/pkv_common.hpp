@@ -41,6 +41,10 @@ hipError_t launch_importance(const pkv_shape& s, const void* q, Strides qs, cons
                              const float* scale, const float* lse, float* importance, void* ws,
                              hipStream_t st);
 
+hipError_t launch_prefill_attn(const pkv_shape& s, const void* q, Strides qs, const void* k, Strides ks,
+                               const void* v, Strides vs, const float* scale, void* out, float* lse,
+                               hipStream_t st);
+
 size_t select_ws_bytes(int B, int L, int N);
 hipError_t launch_select(int B, int L, int N, const float* importance, const pkv_select_params& p,
                          int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,

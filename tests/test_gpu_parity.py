@@ -577,3 +577,38 @@ def test_decode_loop_graph_replays_match_eager(variant):
         assert torch.equal(hp.cache.lens, want_lens), f"replay {rep}"
         # compare occupied slots only (the rest of the buffer is never written)
         assert torch.equal(torch.nan_to_num(hp.cache.kc), torch.nan_to_num(want_kc)), f"replay {rep}"
+
+
+# ------------------------------------------- prefill attention that hands lse to the importance stage
+@pytest.mark.parametrize("B,L,H,Hkv,N,D", [
+    (1, 1, 1, 1, 1, 64), (1, 1, 2, 2, 16, 128), (1, 2, 2, 2, 33, 64), (2, 2, 4, 2, 130, 128),
+    (1, 2, 4, 4, 257, 128), (1, 1, 8, 2, 680, 128), (1, 1, 2, 1, 1100, 64),
+])
+def test_prefill_attention_matches_oracle_and_feeds_importance(B, L, H, Hkv, N, D):
+    g = torch.Generator().manual_seed(N * 7 + D)
+    q = torch.randn((B, L, H, N, D), generator=g).to(torch.bfloat16)
+    k = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    v = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    scale = ((torch.rand(L, generator=g) * 2.5 + 0.5) / D ** 0.5).float()
+    out, lse = P.prefixkv_prefill_attn(q.to(DEV), k.to(DEV), v.to(DEV), scale.to(DEV))
+    want_out, want_lse = oracle.prefill_attn(np32(q), np32(k), np32(v), scale.numpy(), out_bf16=True)
+    torch.cuda.synchronize()
+    assert np.isfinite(np32(out)).all()
+    assert np.abs(np32(out) - want_out).max() <= OUT_ATOL
+    np.testing.assert_allclose(lse.cpu().numpy(), want_lse, rtol=1e-4, atol=2e-4)
+    # the importance stage with this lse (one pass) meets the same bar as with its own (two passes)
+    imp1 = P.prefixkv_importance(q.to(DEV), k.to(DEV), scale.to(DEV), lse=lse)
+    check_importance(imp1.cpu().numpy(), oracle.importance(np32(q), np32(k), scale.numpy()))
+
+
+def test_prefill_attention_strided_inputs_and_refusals():
+    B, L, H, N, D = 1, 2, 2, 70, 128
+    g = torch.Generator().manual_seed(4)
+    big = torch.randn((3, B, L, H, N, D), generator=g).to(torch.bfloat16).to(DEV)   # q, k, v interleaved: strided views
+    q, k, v = big[0], big[1], big[2]
+    scale = torch.full((L,), 0.1, device=DEV)
+    out, lse = P.prefixkv_prefill_attn(q, k, v, scale)
+    ref, ref_lse = P.prefixkv_prefill_attn(q.contiguous(), k.contiguous(), v.contiguous(), scale)
+    assert torch.equal(out, ref) and torch.equal(lse, ref_lse)
+    with pytest.raises(P.PrefixKVError):
+        P.prefixkv_prefill_attn(q.float(), k.float(), v.float(), scale)            # bf16 storage only
