@@ -3,7 +3,8 @@
 // row lse handed over, the importance stage needs one pass over Q K^T instead of two.
 //
 //  prefill_attn_kernel  one workgroup = 128 queries of one (sequence, layer, head); a wavefront owns two
-//                       tiles of 16 queries.  Keys and values stream through LDS 32 rows at a time.  Both
+//                       tiles of 16 queries.  Keys and values stream through LDS 64 rows at a time
+//                       (asynchronous global-to-LDS copies, double-buffered).  Both
 //                       products run on the matrix cores with v_mfma_f32_16x16x32_bf16:
 //                         S^T[16 keys x 16 queries] = K[16 x D] . Q^T            (A = K rows from LDS)
 //                         O^T[16 d    x 16 queries] += V^T[16 d x 32 keys] . P^T (B = the probabilities,
@@ -33,7 +34,8 @@ struct PrefillParams {
 };
 
 constexpr int kPfQueries = 128;   // queries per workgroup (4 wavefronts x 2 tiles x 16)
-constexpr int kPfKeys = 32;       // keys per LDS stage
+constexpr int kPfKeys = 32;       // keys per product V^T . P^T (two S^T tiles)
+constexpr int kPfStage = 64;      // keys per LDS stage
 
 // 4 keys of one column of row-major V: lane r of a 16-lane group points at 4 consecutive columns of key
 // r/4 (columns 4*(r%4) ...); lane i receives column i of keys 0..3.
@@ -42,7 +44,7 @@ __device__ __forceinline__ v4i16_t lds_read_tr(const unsigned char* p) {
 }
 
 template <int D>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)   // two wavefronts per SIMD: at most 256 registers, accumulators included
 prefill_attn_kernel(PrefillParams p) {
     constexpr int ROWB = D * 2;
     constexpr int CPR = D / 8;            // 16-byte chunks per row
@@ -51,8 +53,12 @@ prefill_attn_kernel(PrefillParams p) {
     constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
     // rows are stored unpadded; the 16-byte chunks of row r sit at chunk position c ^ (r & (CPR-1)), which
     // spreads both the fragment reads (16 rows x one chunk) and the transposing reads over all banks
-    __shared__ __attribute__((aligned(16))) unsigned char sK[kPfKeys * ROWB];
-    __shared__ __attribute__((aligned(16))) unsigned char sV[kPfKeys * ROWB];
+    // two statically separate buffer pairs: while one is read, the asynchronous copy of the next stage
+    // fills the other, and the compiler can see that the two do not alias
+    __shared__ __attribute__((aligned(1024))) unsigned char sKa[kPfStage * ROWB];
+    __shared__ __attribute__((aligned(1024))) unsigned char sVa[kPfStage * ROWB];
+    __shared__ __attribute__((aligned(1024))) unsigned char sKb[kPfStage * ROWB];
+    __shared__ __attribute__((aligned(1024))) unsigned char sVb[kPfStage * ROWB];
 
     const int heads = p.B * p.L * p.H;
     const int nqb = (p.N + kPfQueries - 1) / kPfQueries;
@@ -88,20 +94,37 @@ prefill_attn_kernel(PrefillParams p) {
     }
 
     const int last_q = min(p.N, (qb + 1) * kPfQueries) - 1;  // last query of the workgroup
-    const int nst = last_q / kPfKeys + 1;                    // stages that hold a key <= last_q
-    for (int st = 0; st < nst; ++st) {
-        const int key0 = st * kPfKeys;
-        __syncthreads();                                     // the previous stage has been consumed
-        for (int i = threadIdx.x; i < kPfKeys * CPR; i += 256) {
-            const int r = i / CPR, c = i % CPR;
-            int row = key0 + r;
+    const int nst = last_q / kPfStage + 1;                   // stages that hold a key <= last_q
+
+    // asynchronous copy of one stage (keys and values) into a buffer pair: gfx950's 16-byte global-to-LDS
+    // load writes lane i's bytes to LDS[base + 16*i], so one instruction fills 1 KB of consecutive LDS and
+    // the swizzle is applied on the global side
+    constexpr int kInst = kPfStage * ROWB / 1024 / 4;        // copy instructions per wavefront and tensor
+    auto issue = [&](int st, unsigned char* dK, unsigned char* dV) {
+#pragma unroll
+        for (int i = 0; i < kInst; ++i) {
+            const int inst = wv * kInst + i;
+            const int idx = inst * 64 + lane;
+            const int r = idx / CPR, pos = idx % CPR;
+            const int c = pos ^ (r & (CPR - 1));
+            int row = st * kPfStage + r;
             row = row < p.N ? row : p.N - 1;
-            const int pos = c ^ (r & (CPR - 1));
-            *(uint4*)(sK + r * ROWB + pos * 16) = *(const uint4*)(kbase + p.ks.n * row + 8 * c);
-            *(uint4*)(sV + r * ROWB + pos * 16) = *(const uint4*)(vbase + p.vs.n * row + 8 * c);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + p.ks.n * row + 8 * c),
+                                             (__attribute__((address_space(3))) void*)(dK + inst * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + p.vs.n * row + 8 * c),
+                                             (__attribute__((address_space(3))) void*)(dV + inst * 1024), 16, 0, 0);
         }
-        __syncthreads();
-        if (key0 > q0 + 31 || q0 >= p.N) continue;           // every key of the stage is in this wavefront's future
+    };
+
+    auto step = [&](int st, const unsigned char* stK, const unsigned char* stV, unsigned char* nK, unsigned char* nV) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wavefront's part of stage st has landed
+        __syncthreads();                                     // ... and everybody's; the other pair is free again
+        if (st + 1 < nst) issue(st + 1, nK, nV);
+      for (int half = 0; half < kPfStage / kPfKeys; ++half) {
+        const int key0 = st * kPfStage + half * kPfKeys;
+        const unsigned char* sK = stK + half * kPfKeys * ROWB;
+        const unsigned char* sV = stV + half * kPfKeys * ROWB;
+        if (key0 > q0 + 31 || q0 >= p.N) return;             // every further key is in this wavefront's future
         const bool mask = key0 + kPfKeys - 1 > q0 || key0 + kPfKeys > p.N;
 
         // scores S^T = K . Q^T for the two key tiles of the stage and both query tiles
@@ -161,23 +184,32 @@ prefill_attn_kernel(PrefillParams p) {
                 }
             l_run[t] = l_run[t] * corr + psum;
             pf[t] = __builtin_bit_cast(bf16x8_t, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+            if (__builtin_amdgcn_ballot_w64(corr != 1.f)) {      // the running maximum moved for some query
 #pragma unroll
-            for (int dt = 0; dt < NDT; ++dt)
+                for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) o[t][dt][r] *= corr;
+                    for (int r = 0; r < 4; ++r) o[t][dt][r] *= corr;
+            }
         }
         // O^T += V^T . P^T, one product per 16 output columns; the V^T operand serves both query tiles
         const int vr = 4 * kg + (ln >> 2);                   // key (within a 16-key tile) this lane points at
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt) {
-            const int chunk = 2 * dt + ((ln & 3) >> 1), half = (ln & 1) * 8;
-            const v4i16_t a0 = lds_read_tr(sV + vr * ROWB + ((chunk ^ (vr & (CPR - 1))) * 16) + half);
-            const v4i16_t a1 = lds_read_tr(sV + (16 + vr) * ROWB + ((chunk ^ ((16 + vr) & (CPR - 1))) * 16) + half);
+            const int chunk = 2 * dt + ((ln & 3) >> 1), sub8 = (ln & 1) * 8;
+            const v4i16_t a0 = lds_read_tr(sV + vr * ROWB + ((chunk ^ (vr & (CPR - 1))) * 16) + sub8);
+            const v4i16_t a1 = lds_read_tr(sV + (16 + vr) * ROWB + ((chunk ^ ((16 + vr) & (CPR - 1))) * 16) + sub8);
             const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
             for (int t = 0; t < 2; ++t)
                 o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t], o[t][dt], 0, 0, 0);
         }
+      }
+    };
+
+    issue(0, sKa, sVa);
+    for (int st = 0; st < nst; st += 2) {
+        step(st, sKa, sVa, sKb, sVb);
+        if (st + 1 < nst) step(st + 1, sKb, sVb, sKa, sVa);
     }
 
     // epilogue: the four lane groups of a query hold partial row sums; the output tile is transposed
