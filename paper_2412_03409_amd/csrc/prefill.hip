@@ -20,6 +20,8 @@ namespace pkv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef short v4i16_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4i16_t lds_v4i16_t;
 
@@ -36,6 +38,12 @@ struct PrefillParams {
 constexpr int kPfQueries = 128;   // queries per workgroup (4 wavefronts x 2 tiles x 16)
 constexpr int kPfKeys = 32;       // keys per product V^T . P^T (two S^T tiles)
 constexpr int kPfStage = 64;      // keys per LDS stage
+
+// two floats to packed bf16, round to nearest even (the hardware conversion of gfx950)
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    const f32x2_t f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+}
 
 // 4 keys of one column of row-major V: lane r of a 16-lane group points at 4 consecutive columns of key
 // r/4 (columns 4*(r%4) ...); lane i receives column i of keys 0..3.
@@ -180,7 +188,7 @@ prefill_attn_kernel(PrefillParams p) {
                     const float p0 = __builtin_amdgcn_exp2f(s[t][kt][r] - mref);
                     const float p1 = __builtin_amdgcn_exp2f(s[t][kt][r + 1] - mref);
                     psum += p0 + p1;
-                    pk[kt * 2 + r / 2] = (uint32_t)f32_to_bf16(p0) | ((uint32_t)f32_to_bf16(p1) << 16);
+                    pk[kt * 2 + r / 2] = pack_bf16(p0, p1);
                 }
             l_run[t] = l_run[t] * corr + psum;
             pf[t] = __builtin_bit_cast(bf16x8_t, make_uint4(pk[0], pk[1], pk[2], pk[3]));
@@ -225,8 +233,8 @@ prefill_attn_kernel(PrefillParams p) {
         if (kg == 0) p.lse[row] = kLn2 * (m_run[t] + __builtin_amdgcn_logf(lt));
 #pragma unroll
         for (int dt = 0; dt < NDT; ++dt) {
-            const uint32_t w0 = (uint32_t)f32_to_bf16(o[t][dt][0] * inv) | ((uint32_t)f32_to_bf16(o[t][dt][1] * inv) << 16);
-            const uint32_t w1 = (uint32_t)f32_to_bf16(o[t][dt][2] * inv) | ((uint32_t)f32_to_bf16(o[t][dt][3] * inv) << 16);
+            const uint32_t w0 = pack_bf16(o[t][dt][0] * inv, o[t][dt][1] * inv);
+            const uint32_t w1 = pack_bf16(o[t][dt][2] * inv, o[t][dt][3] * inv);
             *(uint2*)(p.out + row * D + 16 * dt + 4 * kg) = make_uint2(w0, w1);
         }
     }
