@@ -111,6 +111,20 @@ def test_rank_and_offline_config_argument_errors():
     assert off(budget=0) == 6
 
 
+def test_prefill_argument_errors():
+    lib = P.load()
+    st = Bd._Strides(4 * 2 * 128 * 64, 2 * 128 * 64, 128 * 64, 64)
+    bf = _shape(dtype=P.PKV_BF16)
+    pf = lambda q=FAKE, lse=FAKE, sh=bf, qs=st: lib.prefixkv_prefill_attn(
+        C.byref(sh), q, qs, FAKE, st, FAKE, st, FAKE, FAKE, lse, None)
+    assert pf(q=None) == 1
+    assert pf(lse=None) == 1
+    assert pf(sh=_shape(D=32, dtype=P.PKV_BF16)) == 2
+    assert pf(sh=_shape()) == 7               # fp32 storage is not provided
+    assert pf(qs=Bd._Strides(0, 0, 0, 6)) == 4
+    assert pf(q=C.c_void_p(0x1004)) == 4
+
+
 def test_gini_and_merge_argument_errors():
     lib = P.load()
     assert lib.prefixkv_gini(1, 4, 128, None, FAKE, None) == 1

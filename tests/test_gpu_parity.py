@@ -601,6 +601,23 @@ def test_prefill_attention_matches_oracle_and_feeds_importance(B, L, H, Hkv, N, 
     check_importance(imp1.cpu().numpy(), oracle.importance(np32(q), np32(k), scale.numpy()))
 
 
+def test_prefill_attention_negative_scale_and_sinks():
+    """A negative logit scale (moved into the queries by the kernel) and large sink keys that make the
+    running maximum jump late in the row."""
+    B, L, H, Hkv, N, D = 1, 2, 2, 2, 200, 128
+    g = torch.Generator().manual_seed(12)
+    q = torch.randn((B, L, H, N, D), generator=g).to(torch.bfloat16)
+    k = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    v = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    k[..., 150, :] *= 4
+    k[..., 0, :] *= 3
+    scale = torch.tensor([-0.11, 0.2])
+    out, lse = P.prefixkv_prefill_attn(q.to(DEV), k.to(DEV), v.to(DEV), scale.to(DEV))
+    want_out, want_lse = oracle.prefill_attn(np32(q), np32(k), np32(v), scale.numpy(), out_bf16=True)
+    assert np.abs(np32(out) - want_out).max() <= OUT_ATOL
+    np.testing.assert_allclose(lse.cpu().numpy(), want_lse, rtol=1e-4, atol=2e-4)
+
+
 def test_prefill_attention_strided_inputs_and_refusals():
     B, L, H, N, D = 1, 2, 2, 70, 128
     g = torch.Generator().manual_seed(4)
