@@ -67,6 +67,9 @@ int prefixkv_importance(const pkv_shape* s, const void* q, pkv_strides qs, const
     const int esize = s->dtype == PKV_F32 ? 4 : 2;
     if (!strides_ok(qs, esize) || !strides_ok(ks, esize) || !aligned16(q) || !aligned16(k))
         return PKV_ERR_STRIDE;
+    // the bf16 kernels address the rows of one head with 32-bit element offsets
+    if ((uint64_t)s->N * (uint64_t)qs.n >= (1ull << 31) || (uint64_t)s->N * (uint64_t)ks.n >= (1ull << 31))
+        return PKV_ERR_UNSUPPORTED;
     if (!ws || ws_bytes < importance_ws_bytes(*s, lse != nullptr)) return PKV_ERR_WORKSPACE;
     const hipError_t e = launch_importance(*s, q, to_strides(qs), k, to_strides(ks), scale, lse, importance,
                                            ws, (hipStream_t)stream);
@@ -84,6 +87,8 @@ int prefixkv_prefill_attn(const pkv_shape* s, const void* q, pkv_strides qs, con
         !aligned16(v) || !aligned16(out))
         return PKV_ERR_STRIDE;
     if ((size_t)s->B * s->L * s->H * ((s->N + 127) / 128) > 0x7fffffffull) return PKV_ERR_UNSUPPORTED;
+    if ((uint64_t)s->N * (uint64_t)ks.n >= (1ull << 31) || (uint64_t)s->N * (uint64_t)vs.n >= (1ull << 31))
+        return PKV_ERR_UNSUPPORTED;   // rows of one head are addressed with 32-bit element offsets
     const hipError_t e = launch_prefill_attn(*s, q, to_strides(qs), k, to_strides(ks), v, to_strides(vs), scale, out,
                                              lse, (hipStream_t)stream);
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;

@@ -80,7 +80,8 @@ template <int D> struct Stage {
             const int c = pos ^ ((row / RPB) & (CPR - 1));
             int grow = row0 + row;
             grow = grow < N ? grow : N - 1;
-            const bf16_t* g = base + (int64_t)grow * ld + c * 8;
+            // 32-bit element offset from the uniform base of this head (N * ld < 2^31, checked by the launcher)
+            const bf16_t* g = base + ((uint32_t)grow * (uint32_t)ld + (uint32_t)(c * 8));
             __builtin_amdgcn_global_load_lds((glb_void_t*)g, (lds_void_t*)(lds + inst * 1024), 16, 0, 0);
         }
     }

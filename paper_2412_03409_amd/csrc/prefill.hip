@@ -128,14 +128,15 @@ prefill_attn_kernel(PrefillParams p) {
         cp_row[i] = r;
         cp_col[i] = 8 * (pos ^ swz<CPR>(r));
     }
+    const uint32_t ksn = (uint32_t)p.ks.n, vsn = (uint32_t)p.vs.n;   // N * stride < 2^31, checked by the launcher
     auto issue = [&](int st, unsigned char* dK, unsigned char* dV) {
 #pragma unroll
         for (int i = 0; i < kInst; ++i) {
             int row = st * kPfStage + cp_row[i];
             row = row < p.N ? row : p.N - 1;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + p.ks.n * row + cp_col[i]),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + ((uint32_t)row * ksn + (uint32_t)cp_col[i])),
                                              (__attribute__((address_space(3))) void*)(dK + (wv * kInst + i) * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + p.vs.n * row + cp_col[i]),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + ((uint32_t)row * vsn + (uint32_t)cp_col[i])),
                                              (__attribute__((address_space(3))) void*)(dV + (wv * kInst + i) * 1024), 16, 0, 0);
         }
     };
