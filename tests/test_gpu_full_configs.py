@@ -190,3 +190,33 @@ def test_llava7b_b1_pruning_decode():
 
 def test_llava7b_b16_pruning_decode_sampled_sequence():
     run_config_pruning("llava7b_b16", 0.2, sample_b=7, steps=12, d=5)
+
+
+@pytest.mark.parametrize("name,layers", [("llava7b_b1", [0, 17, 31]), ("gqa_long", [5])])
+def test_prefill_attention_feeds_one_pass_importance_at_full_size(name, layers):
+    """Prefill attention at the benchmark shapes: output and lse of sampled layers against the oracle (for the
+    long prompt only the rows of the last block are cheap enough for the CPU, so the check there is the
+    one-pass importance of the tail columns), and the importance computed from that lse against the
+    two-pass importance of the library itself."""
+    w = CONFIGS[name]
+    if name == "gqa_long":
+        w = w.with_(B=1, L=8)
+    x = make_prefill(w, device=DEV)
+    out, lse = P.prefixkv_prefill_attn(x["q"], x["k"], x["v"], x["scale"])
+    imp1 = P.prefixkv_importance(x["q"], x["k"], x["scale"], lse=lse)
+    imp2 = P.prefixkv_importance(x["q"], x["k"], x["scale"])
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    check_importance(imp1.cpu().numpy(), imp2.cpu().numpy())
+    scale = x["scale"].cpu().numpy()
+    for l in layers:
+        sl = slice(l, l + 1)
+        if name == "llava7b_b1":
+            want_out, want_lse = oracle.prefill_attn(f32(x["q"][:1, sl]), f32(x["k"][:1, sl]), f32(x["v"][:1, sl]),
+                                                     scale[sl], out_bf16=True)
+            assert np.abs(f32(out[:1, sl]) - want_out).max() <= OUT_ATOL
+            np.testing.assert_allclose(lse[:1, sl].cpu().numpy(), want_lse, rtol=1e-4, atol=3e-4)
+        else:
+            m_lo = w.N - 96
+            want = oracle.importance(f32(x["q"][:1, sl]), f32(x["k"][:1, sl]), scale[sl], m_lo=m_lo)
+            check_importance(imp1[:1, sl, m_lo:].cpu().numpy(), want[..., m_lo:])
