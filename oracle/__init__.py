@@ -232,6 +232,54 @@ def merge_position(cache, k, v, storage_bf16: bool = False):
     return cache
 
 
+def feature_match(cache, x):
+    """Feature-similarity matching of one tensor x [B,L,Hkv,N,D] (keys or values) against the retained set of a
+    cache dict from compact(): match [B,L,Hkv,N] i32 (slot for a pruned position, -1 for a retained one) and the
+    cosine of that best pair [B,L,Hkv,N] f64."""
+    x = _f32(x)
+    B, L, Hkv, N, D = x.shape
+    assert cache["Hkv"] == Hkv and cache["D"] == D
+    match = np.zeros((B, L, Hkv, N), np.int32)
+    best = np.zeros((B, L, Hkv, N), np.float64)
+    lib().pkvo_feature_match(B, L, Hkv, N, D, _p(x), _p(cache["seg_off"]), _p(cache["kept_pos"]),
+                             _p(cache["lens"]), _p(match), _p(best))
+    return match, best
+
+
+def match_cosine(cache, x, match):
+    """Cosine of every pruned position of x with the retained vector that `match` assigns it to (1 where -1)."""
+    x = _f32(x)
+    B, L, Hkv, N, D = x.shape
+    match = np.ascontiguousarray(match, dtype=np.int32)
+    assert match.shape == (B, L, Hkv, N)
+    out = np.zeros((B, L, Hkv, N), np.float64)
+    lib().pkvo_match_cosine(B, L, Hkv, N, D, _p(x), _p(cache["seg_off"]), _p(cache["kept_pos"]), _p(match), _p(out))
+    return out
+
+
+def merge_by_match(cache, name: str, x, match, storage_bf16: bool = False):
+    """Replace every retained vector of cache[name] ('kc' or 'vc') by the average of itself and the pruned
+    vectors of x that `match` assigns to its slot; in place."""
+    x = _f32(x)
+    B, L, Hkv, N, D = x.shape
+    match = np.ascontiguousarray(match, dtype=np.int32)
+    assert match.shape == (B, L, Hkv, N) and name in ("kc", "vc")
+    lib().pkvo_merge_by_match(B, L, Hkv, N, D, _p(x), _p(cache["seg_off"]), _p(cache["caps"]),
+                              _p(cache["kept_pos"]), _p(cache["lens"]), _p(match), _p(cache[name]),
+                              int(storage_bf16))
+    return cache
+
+
+def merge_feature(cache, k, v, storage_bf16: bool = False):
+    """Feature-similarity merging of keys (by key cosine) and values (by value cosine), in place on a cache dict
+    from compact(); returns the two assignments."""
+    mk, _ = feature_match(cache, k)
+    mv, _ = feature_match(cache, v)
+    merge_by_match(cache, "kc", k, mk, storage_bf16)
+    merge_by_match(cache, "vc", v, mv, storage_bf16)
+    return mk, mv
+
+
 def segment(cache, name: str, b: int, l: int):
     """View of segment (b,l) of 'kc'/'vc' as [Hkv, cap, D], or of 'kept_pos' as [cap]."""
     off = int(cache["seg_off"][b, l])

@@ -592,6 +592,100 @@ void pkvo_merge_position(int B, int L, int Hkv, int N, int D, const float *k, co
 }
 
 /* ---------------------------------------------------------------------------------------------
+ * Cache merging by feature similarity (Sec. 4.3, "Eviction or merging", the variant called "Feature":
+ * matching metric c^{mn} = cosine of the pruned vector m and the retained vector n).  The paper
+ * describes the operation on the key vectors of one head and says that values and the other heads
+ * are treated the same way; the reading taken here is the literal one: every (head, tensor) pair is
+ * merged on its own, with the cosine of ITS vectors (keys by key similarity, values by value
+ * similarity).  A vector of norm zero has cosine 0 with everything.
+ *
+ * pkvo_feature_match: x [B,L,Hkv,N,D] (keys OR values, uncompressed); the retained set of (b,l) is
+ * kept_pos[seg_off .. +lens) (ascending positions).  match [B,L,Hkv,N] gets, for a pruned position,
+ * the slot of the retained vector with the largest cosine (first maximum = lowest position), for a
+ * retained position -1; best (may be NULL) gets that largest cosine (1 for retained positions).
+ * pkvo_match_cosine: the cosine of every pruned position with the slot a GIVEN assignment names
+ * (what a test needs to accept a different but equally good choice on a near tie).
+ * pkvo_merge_by_match: slot j of the compressed tensor xc := average of the retained vector and of all
+ * pruned vectors assigned to it, in fp64, rounded to bfloat16 if storage_bf16.
+ * ------------------------------------------------------------------------------------------- */
+static double pkvo_cosine(const float *a, const float *b, int D) {
+    double dot = 0.0, na = 0.0, nb = 0.0;
+    for (int x = 0; x < D; ++x) {
+        dot += (double)a[x] * (double)b[x];
+        na += (double)a[x] * (double)a[x];
+        nb += (double)b[x] * (double)b[x];
+    }
+    return (na > 0.0 && nb > 0.0) ? dot / (sqrt(na) * sqrt(nb)) : 0.0;
+}
+
+void pkvo_feature_match(int B, int L, int Hkv, int N, int D, const float *x, const int64_t *seg_off,
+                        const int32_t *kept_pos, const int32_t *lens, int32_t *match, double *best) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < (long)B * L * Hkv; ++u) {
+        const long bl = u / Hkv;
+        const int n = lens[bl];
+        const int32_t *kp = kept_pos + seg_off[bl];
+        const float *xh = x + (size_t)u * N * D;
+        int32_t *mt = match + (size_t)u * N;
+        for (int m = 0; m < N; ++m) {
+            int arg = 0;
+            double top = -INFINITY;
+            for (int j = 0; j < n; ++j) {
+                const double c = pkvo_cosine(xh + (size_t)m * D, xh + (size_t)kp[j] * D, D);
+                if (c > top) { top = c; arg = j; }
+            }
+            mt[m] = arg;
+            if (best) best[(size_t)u * N + m] = top;
+        }
+        for (int j = 0; j < n; ++j) {
+            mt[kp[j]] = -1;
+            if (best) best[(size_t)u * N + kp[j]] = 1.0;
+        }
+    }
+}
+
+void pkvo_match_cosine(int B, int L, int Hkv, int N, int D, const float *x, const int64_t *seg_off,
+                       const int32_t *kept_pos, const int32_t *match, double *cosine) {
+    for (long u = 0; u < (long)B * L * Hkv; ++u) {
+        const int32_t *kp = kept_pos + seg_off[u / Hkv];
+        const float *xh = x + (size_t)u * N * D;
+        for (int m = 0; m < N; ++m) {
+            const int j = match[(size_t)u * N + m];
+            cosine[(size_t)u * N + m] = j < 0 ? 1.0 : pkvo_cosine(xh + (size_t)m * D, xh + (size_t)kp[j] * D, D);
+        }
+    }
+}
+
+void pkvo_merge_by_match(int B, int L, int Hkv, int N, int D, const float *x, const int64_t *seg_off,
+                         const int32_t *caps, const int32_t *kept_pos, const int32_t *lens,
+                         const int32_t *match, float *xc, int storage_bf16) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < (long)B * L * Hkv; ++u) {
+        const long bl = u / Hkv;
+        const int h = (int)(u % Hkv), n = lens[bl];
+        const int32_t *kp = kept_pos + seg_off[bl];
+        const float *xh = x + (size_t)u * N * D;
+        const int32_t *mt = match + (size_t)u * N;
+        float *dst = xc + ((size_t)seg_off[bl] * Hkv + (size_t)h * caps[bl]) * D;
+        double *acc = (double *)malloc(sizeof(double) * (size_t)D);
+        for (int j = 0; j < n; ++j) {
+            int cnt = 1;
+            for (int d = 0; d < D; ++d) acc[d] = (double)xh[(size_t)kp[j] * D + d];
+            for (int m = 0; m < N; ++m)
+                if (mt[m] == j) {
+                    ++cnt;
+                    for (int d = 0; d < D; ++d) acc[d] += (double)xh[(size_t)m * D + d];
+                }
+            for (int d = 0; d < D; ++d) {
+                const double mean = acc[d] / (double)cnt;
+                dst[(size_t)j * D + d] = storage_bf16 ? pkvo_round_bf16(mean) : (float)mean;
+            }
+        }
+        free(acc);
+    }
+}
+
+/* ---------------------------------------------------------------------------------------------
  * Causal prefill attention of one prompt (Sec. 3.1: the prefill phase computes the attention of all
  * prompt tokens; Sec. 3.2 builds the importance from the same score matrix a_l^{i,m,n}).
  *   out[m] = sum_{n<=m} a[m][n] * v[n],  a[m][n] = exp(scale*q_m.k_n) / sum_{j<=m} exp(scale*q_m.k_j)

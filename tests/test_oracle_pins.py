@@ -702,6 +702,98 @@ def test_merge_position_is_nearest_kept_average():
     assert ((kc.view(np.uint32) & 0xffff) == 0).all()
 
 
+def test_merge_feature_is_cosine_argmax_average():
+    """Brute force in NumPy (normalised rows, one matrix product, first maximum); keys and values are matched
+    on their own; the groups partition all positions (mass conservation); cosine is scale-free."""
+    k, v, sel, cache = make_cache_case(94, B=2, L=2, Hkv=2, N=29, D=8, cap=2, frac=0.3)
+    r = np.random.default_rng(95)
+    k *= r.uniform(0.1, 30.0, k.shape[:-1] + (1,)).astype(np.float32)       # norms all over the place
+    cache = oracle.compact(k, v, sel["order"], sel["lengths"], 2)
+    mk, mv = oracle.merge_feature(cache, k, v)
+    mk2, best = oracle.feature_match(cache, k)
+    np.testing.assert_array_equal(mk, mk2)
+    np.testing.assert_allclose(oracle.match_cosine(cache, k, mk), best, rtol=0, atol=0)
+    B, L, Hkv, N, D = k.shape
+    assert not np.array_equal(mk, mv)
+    for b in range(B):
+        for l in range(L):
+            n = int(sel["lengths"][b, l])
+            kp = oracle.segment(cache, "kept_pos", b, l)[:n]
+            pruned = np.setdiff1d(np.arange(N), kp)
+            for name, src, match in (("kc", k, mk), ("vc", v, mv)):
+                seg = oracle.segment(cache, name, b, l)
+                for h in range(Hkv):
+                    x = src[b, l, h].astype(np.float64)
+                    xn = x / np.linalg.norm(x, axis=1, keepdims=True)
+                    cos = xn[pruned] @ xn[kp].T
+                    want = cos.argmax(1)
+                    got = match[b, l, h]
+                    assert (got[kp] == -1).all()
+                    np.testing.assert_array_equal(got[pruned], want)
+                    np.testing.assert_allclose(best[b, l, h][pruned], cos.max(1), rtol=1e-12) if name == "kc" else None
+                    counts = 1 + np.bincount(want, minlength=n)
+                    for j in range(n):
+                        mean = (x[kp[j]] + x[pruned[want == j]].sum(0)) / counts[j]
+                        np.testing.assert_allclose(seg[h, j], mean, rtol=1e-6, atol=1e-6)
+                    mass = (seg[h, :n].astype(np.float64) * counts[:, None]).sum(0)
+                    np.testing.assert_allclose(mass, x.sum(0), rtol=1e-5, atol=1e-4)
+                    assert np.isnan(seg[h, n:]).all()
+
+
+def test_merge_feature_special_cases():
+    """(a) Vectors on a circle whose angle grows (slightly convexly) with the position: the most similar
+    retained vector is the nearest in position, the lower one half way, whatever the lengths of the vectors --
+    the result is that of positional merging.  (b) A pruned vector that is a positive multiple of a retained one
+    goes to it, with cosine 1.  (c) A zero vector has cosine 0 with everything; among all-zero vectors it goes to slot 0
+    (first maximum); a vector opposite to every retained one still goes to the least bad.  (d) Full budget: nothing
+    changes.  (e) bf16 storage gives bf16-representable averages."""
+    N, n_l = 41, 2
+    r = np.random.default_rng(96)
+    theta = 0.02 * np.arange(N) ** 1.001
+    rad = r.uniform(0.2, 5.0, N)
+    x = np.zeros((1, n_l, 1, N, 2), np.float32)
+    x[0, :, 0, :, 0] = (rad * np.cos(theta))[None]
+    x[0, :, 0, :, 1] = (rad * np.sin(theta))[None]
+    imp = r.random((1, n_l, N)).astype(np.float32) + 0.01
+    sel = oracle.select(imp, 14)
+    c_feat = oracle.compact(x, x, sel["order"], sel["lengths"], 0)
+    c_pos = oracle.compact(x, x, sel["order"], sel["lengths"], 0)
+    oracle.merge_feature(c_feat, x, x)
+    oracle.merge_position(c_pos, x, x)
+    np.testing.assert_allclose(c_feat["kc"], c_pos["kc"], rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(c_feat["vc"], c_pos["vc"], rtol=1e-6, atol=1e-7)
+    # (b), (c)
+    k = r.standard_normal((1, 1, 1, 6, 4)).astype(np.float32)
+    k[0, 0, 0, 4] = 2.5 * k[0, 0, 0, 1]
+    k[0, 0, 0, 5] = 0.0
+    order = np.array([[[0, 1, 2, 3, 4, 5]]], np.int32)
+    cache = oracle.compact(k, k, order, np.array([[3]], np.int32), 0)
+    match, best = oracle.feature_match(cache, k)
+    assert match[0, 0, 0].tolist()[:3] == [-1, -1, -1] and match[0, 0, 0, 4] == 1
+    assert abs(best[0, 0, 0, 4] - 1.0) < 1e-12 and best[0, 0, 0, 5] == 0.0
+    kz = np.zeros((1, 1, 1, 4, 4), np.float32)
+    cz = oracle.compact(kz, kz, np.array([[[2, 1, 0, 3]]], np.int32), np.array([[2]], np.int32), 0)
+    mz, bz = oracle.feature_match(cz, kz)
+    assert mz[0, 0, 0].tolist() == [0, -1, -1, 0] and (bz[0, 0, 0, [0, 3]] == 0).all()
+    # an opposite vector (cosine -1) still goes to the better of the bad choices
+    ko = np.array([[[[[1, 0], [0, 1], [-1, -0.1]]]]], np.float32)
+    co = oracle.compact(ko, ko, np.array([[[0, 1, 2]]], np.int32), np.array([[2]], np.int32), 0)
+    mo, bo = oracle.feature_match(co, ko)
+    assert mo[0, 0, 0, 2] == 1 and bo[0, 0, 0, 2] < 0
+    # (d)
+    kf, vf, self_, cf = make_cache_case(97, frac=1.0, cap=0)
+    ref = {n: cf[n].copy() for n in ("kc", "vc")}
+    mk, mv = oracle.merge_feature(cf, kf, vf)
+    assert (mk == -1).all() and (mv == -1).all()
+    np.testing.assert_array_equal(cf["kc"], ref["kc"])
+    np.testing.assert_array_equal(cf["vc"], ref["vc"])
+    # bf16 storage
+    kb, vb, selb, cb = make_cache_case(98, frac=0.4)
+    oracle.merge_feature(cb, kb, vb, storage_bf16=True)
+    kc = cb["kc"][~np.isnan(cb["kc"])]
+    assert ((kc.view(np.uint32) & 0xffff) == 0).all()
+
+
 # ------------------------------------------------------------------ causal prefill attention
 def test_prefill_attention_matches_dense_numpy_and_ties_to_importance():
     """Dense masked softmax in NumPy (incl. GQA and per-layer scale); constant V gives that constant; with
