@@ -68,7 +68,7 @@ const char *prefixkv_status_string(int status);
 /* Workspace bytes for op = PKV_OP_*.  `has_lse` (PKV_OP_IMPORTANCE only) = the caller will pass
  * its own lse.  Returns 0 for invalid arguments and for stages that need no scratch (compaction;
  * decode attention unless several query heads share a KV head in a bf16 cache): ws may then be NULL. */
-enum { PKV_OP_IMPORTANCE = 0, PKV_OP_SELECT = 1, PKV_OP_COMPACT = 2, PKV_OP_DECODE = 3 };
+enum { PKV_OP_IMPORTANCE = 0, PKV_OP_SELECT = 1, PKV_OP_COMPACT = 2, PKV_OP_DECODE = 3, PKV_OP_MERGE_FEATURE = 4 };
 size_t prefixkv_workspace_bytes(int op, const pkv_shape *shape, int has_lse);
 
 /* ---- Stage 1: KV importance (Sec. 3.2, the causal score matrix a_l^{i,m,n} and the importance
@@ -186,11 +186,33 @@ int prefixkv_compact(const pkv_shape *shape, const void *k, pkv_strides ks, cons
  * (first maximum of the metric); keys and values of all KV heads are averaged alike, fp32 sums in
  * ascending position, one rounding to the storage dtype.  Only the first lens[b,l] slots are written.
  *   k, v [dev]: the uncompressed tensors given to prefixkv_compact;  everything else as produced by it.
- * The feature-similarity variant ("Feature") is not provided. */
+ * prefixkv_merge_feature is the variant with the cosine metric. */
 int prefixkv_merge_position(const pkv_shape *shape, const void *k, pkv_strides ks, const void *v,
                             pkv_strides vs, const int64_t *seg_off, const int32_t *caps,
                             const int32_t *kept_pos, const int32_t *lens, void *kc, void *vc,
                             pkv_stream stream);
+
+/* ---- Cache merging by feature similarity (Sec. 4.3, "Eviction or merging", the variant the paper calls
+ * "Feature": matching metric c^{mn} = cosine of the pruned vector m and the retained vector n; every
+ * retained vector becomes the average of itself and the pruned vectors whose largest metric it holds).
+ * The paper spells the operation out for the keys of one head and treats values and the other heads
+ * "the same"; the reading implemented is the literal one: each (kv head, tensor) pair is matched and
+ * merged on its own -- keys by the cosine of keys, values by the cosine of values.
+ * Runs in place on the output of prefixkv_compact, before the first decode step, like
+ * prefixkv_merge_position.  bf16 storage only (PKV_ERR_UNSUPPORTED otherwise); N * row stride of k and
+ * of v must be below 2^31 elements.
+ *   Decision arithmetic: dot products of the bf16 vectors accumulated in fp32 on the matrix cores,
+ *   times the fp32 reciprocal norm of the retained vector (the norm of the pruned vector is common to
+ *   all its candidates and left out); a vector of norm zero has metric 0 with everything; among equal
+ *   metrics the retained vector at the lowest position wins.  Sums of a group are taken in fp32 in a
+ *   fixed order, one rounding to bf16.
+ *   match [dev] i32 [2,B,L,Hkv,N] (out): plane 0 for keys, 1 for values; the slot a pruned position
+ *       was merged into, -1 for a retained position.
+ *   ws [dev]: prefixkv_workspace_bytes(PKV_OP_MERGE_FEATURE, shape, 0) bytes (the reciprocal norms). */
+int prefixkv_merge_feature(const pkv_shape *shape, const void *k, pkv_strides ks, const void *v,
+                           pkv_strides vs, const int64_t *seg_off, const int32_t *caps,
+                           const int32_t *kept_pos, const int32_t *lens, void *kc, void *vc,
+                           int32_t *match, void *ws, size_t ws_bytes, pkv_stream stream);
 
 /* ---- Diagnostic: Gini coefficient of every layer's priority sequence (Sec. 4.3, "Relation between KV
  * cache size and importance distribution": layers with a more concentrated distribution, i.e. a higher

@@ -17,7 +17,7 @@ _HERE = Path(__file__).resolve().parent
 _LIB_PATH = _HERE / "libprefixkv.so"
 
 PKV_F32, PKV_BF16 = 0, 1
-OP_IMPORTANCE, OP_SELECT, OP_COMPACT, OP_DECODE = 0, 1, 2, 3
+OP_IMPORTANCE, OP_SELECT, OP_COMPACT, OP_DECODE, OP_MERGE_FEATURE = 0, 1, 2, 3, 4
 
 
 class PrefixKVError(RuntimeError):
@@ -79,6 +79,9 @@ def load(path: Optional[str] = None) -> C.CDLL:
     L.prefixkv_gini.argtypes = [i32, i32, i32, vp, vp, vp]
     L.prefixkv_merge_position.restype = C.c_int
     L.prefixkv_merge_position.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, vp, vp, vp, vp, vp]
+    L.prefixkv_merge_feature.restype = C.c_int
+    L.prefixkv_merge_feature.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, vp, vp, vp, vp, vp,
+                                         vp, sz, vp]
     L.prefixkv_compact.restype = C.c_int
     L.prefixkv_compact.argtypes = [C.POINTER(_Shape), vp, _Strides, vp, _Strides, vp, vp, i32, vp, vp, vp,
                                    vp, vp, vp, vp, sz, vp]
@@ -351,6 +354,30 @@ def prefixkv_merge_position(cache: CompactResult, k: torch.Tensor, v: torch.Tens
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_merge_position")
     return cache
+
+
+def prefixkv_merge_feature(cache: CompactResult, k: torch.Tensor, v: torch.Tensor,
+                           match: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Average every pruned vector into the most similar (cosine) retained vector of its head, keys by key
+    similarity and values by value similarity, in place on a freshly compacted bf16 cache.  Returns the
+    assignment match [2,B,L,Hkv,N] i32 (plane 0 keys, 1 values; -1 at retained positions)."""
+    _need_cuda(k, v, match, ws)
+    B, L, Hkv, N, D = k.shape
+    if v.shape != k.shape or v.dtype != k.dtype or k.dtype != cache.kc.dtype or D != cache.D or Hkv != cache.Hkv:
+        raise ValueError("k, v must be the [B,L,Hkv,N,D] tensors the cache was compacted from")
+    if match is None:
+        match = torch.empty((2, B, L, Hkv, N), dtype=torch.int32, device=k.device)
+    elif match.dtype != torch.int32 or tuple(match.shape) != (2, B, L, Hkv, N) or not match.is_contiguous():
+        raise ValueError("match must be contiguous i32 [2,B,L,Hkv,N]")
+    s = _shape(B, L, Hkv, Hkv, N, D, _dtype_code(k))
+    w = _ws(load().prefixkv_workspace_bytes(OP_MERGE_FEATURE, C.byref(s), 0), k.device, ws)
+    rc = load().prefixkv_merge_feature(C.byref(s), _ptr(k), _strides5(k), _ptr(v), _strides5(v),
+                                       _ptr(cache.seg_off), _ptr(cache.caps), _ptr(cache.kept_pos),
+                                       _ptr(cache.lens), _ptr(cache.kc), _ptr(cache.vc), _ptr(match), _ptr(w),
+                                       w.numel() * w.element_size(), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_merge_feature")
+    return match
 
 
 def prefixkv_gini(cum: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

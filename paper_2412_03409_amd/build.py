@@ -10,7 +10,7 @@ from pathlib import Path
 HERE = Path(__file__).resolve().parent
 CSRC = HERE / "csrc"
 LIB = HERE / "libprefixkv.so"
-SOURCES = ["api.hip", "importance.hip", "select.hip", "compact.hip", "decode.hip", "prefill.hip"]
+SOURCES = ["api.hip", "importance.hip", "select.hip", "compact.hip", "decode.hip", "prefill.hip", "merge_feature.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=on",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]

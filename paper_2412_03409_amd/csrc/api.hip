@@ -54,6 +54,7 @@ size_t prefixkv_workspace_bytes(int op, const pkv_shape* s, int has_lse) {
         case PKV_OP_SELECT: return select_ws_bytes(s->B, s->L, s->N);
         case PKV_OP_COMPACT: return compact_ws_bytes(*s);
         case PKV_OP_DECODE: return decode_ws_bytes(*s);
+        case PKV_OP_MERGE_FEATURE: return merge_feature_ws_bytes(*s);
         default: return 0;
     }
 }
@@ -167,6 +168,27 @@ int prefixkv_merge_position(const pkv_shape* s, const void* k, pkv_strides ks, c
     if ((size_t)8 * s->Hkv * s->B * s->L > 0x7fffffffull) return PKV_ERR_UNSUPPORTED;
     const hipError_t e = launch_merge_position(*s, k, to_strides(ks), v, to_strides(vs), seg_off, caps, kept_pos,
                                                lens, kc, vc, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int prefixkv_merge_feature(const pkv_shape* s, const void* k, pkv_strides ks, const void* v, pkv_strides vs,
+                           const int64_t* seg_off, const int32_t* caps, const int32_t* kept_pos,
+                           const int32_t* lens, void* kc, void* vc, int32_t* match, void* ws, size_t ws_bytes,
+                           pkv_stream stream) {
+    if (!s || !k || !v || !seg_off || !caps || !kept_pos || !lens || !kc || !vc || !match) return PKV_ERR_NULL;
+    if (!shape_ok(s)) return PKV_ERR_DIM;
+    if (!dtype_ok(s)) return PKV_ERR_DTYPE;
+    if (s->dtype != PKV_BF16) return PKV_ERR_UNSUPPORTED;
+    if (!strides_ok(ks, 2) || !strides_ok(vs, 2) || !aligned16(k) || !aligned16(v) || !aligned16(kc) ||
+        !aligned16(vc))
+        return PKV_ERR_STRIDE;
+    // the kernels address rows with 32-bit element offsets, and their grids are one-dimensional
+    if ((int64_t)s->N * ks.n > 0x7fffffffll || (int64_t)s->N * vs.n > 0x7fffffffll ||
+        (size_t)2 * 64 * s->Hkv * s->B * s->L > 0x7fffffffull)
+        return PKV_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < merge_feature_ws_bytes(*s) || !aligned16(ws)) return PKV_ERR_WORKSPACE;
+    const hipError_t e = launch_merge_feature(*s, k, to_strides(ks), v, to_strides(vs), seg_off, caps, kept_pos,
+                                              lens, kc, vc, match, ws, (hipStream_t)stream);
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
 

@@ -60,6 +60,12 @@ hipError_t launch_merge_position(const pkv_shape& s, const void* k, Strides ks, 
                                  const int64_t* seg_off, const int32_t* caps, const int32_t* kept_pos,
                                  const int32_t* lens, void* kc, void* vc, hipStream_t st);
 
+size_t merge_feature_ws_bytes(const pkv_shape& s);
+hipError_t launch_merge_feature(const pkv_shape& s, const void* k, Strides ks, const void* v, Strides vs,
+                                const int64_t* seg_off, const int32_t* caps, const int32_t* kept_pos,
+                                const int32_t* lens, void* kc, void* vc, int32_t* match, void* ws,
+                                hipStream_t st);
+
 size_t compact_ws_bytes(const pkv_shape& s);
 hipError_t launch_compact(const pkv_shape& s, const void* k, Strides ks, const void* v, Strides vs,
                           const int32_t* order, const int32_t* lengths, int decode_capacity,

@@ -142,6 +142,25 @@ def test_gini_and_merge_argument_errors():
     assert mg(k=C.c_void_p(0x1004)) == 4
 
 
+def test_merge_feature_argument_errors():
+    lib = P.load()
+    st = Bd._Strides(4 * 2 * 128 * 64, 2 * 128 * 64, 128 * 64, 64)
+    bf = _shape(dtype=P.PKV_BF16)
+    need = lib.prefixkv_workspace_bytes(P.binding.OP_MERGE_FEATURE, C.byref(bf), 0)
+    assert need == 2 * bf.B * bf.L * bf.Hkv * ((bf.N + 63) // 64 * 64) * 4
+    mf = lambda k=FAKE, mt=FAKE, sh=bf, ks=st, ws=FAKE, nb=need: lib.prefixkv_merge_feature(
+        C.byref(sh), k, ks, FAKE, st, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, mt, ws, nb, None)
+    assert mf(k=None) == 1
+    assert mf(mt=None) == 1
+    assert mf(sh=_shape(D=32, dtype=P.PKV_BF16)) == 2
+    assert mf(sh=_shape(dtype=7)) == 3
+    assert mf(sh=_shape()) == 7                      # fp32 storage is not provided
+    assert mf(ks=Bd._Strides(0, 0, 0, 6)) == 4
+    assert mf(ks=Bd._Strides(0, 0, 0, 1 << 24)) == 7  # rows beyond 31-bit element offsets
+    assert mf(ws=None) == 5
+    assert mf(nb=need - 1) == 5
+
+
 def test_compact_and_decode_argument_errors():
     lib = P.load()
     st = Bd._Strides(4 * 2 * 128 * 64, 2 * 128 * 64, 128 * 64, 64)

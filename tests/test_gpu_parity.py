@@ -265,6 +265,72 @@ def check_cache(got, want, dtype):
             np.testing.assert_array_equal(gv, oracle.segment(want, "vc", b, l)[:, :n])
 
 
+@pytest.mark.parametrize("B,L,Hkv,N,D,frac", [
+    (1, 2, 2, 128, 64, 0.5),
+    (2, 3, 4, 333, 128, 0.2),
+    (2, 2, 2, 70, 64, 0.33),
+    (1, 2, 2, 100, 128, 1.0),          # full budget: nothing to merge
+    (1, 2, 2, 97, 128, 0.03),          # one or two retained vectors take everything
+    (1, 2, 1, 2100, 128, 0.15),        # several position blocks and LDS stages, ragged tails
+    (1, 1, 2, 8192, 64, 0.1),
+])
+def test_merge_feature_matches_oracle(B, L, Hkv, N, D, frac):
+    """Feature-similarity merging (Sec. 4.3, cosine metric).  The assignment is an argmax decided in the
+    kernel's fp32: it must be as good as the oracle's within the rounding of that arithmetic, identical on the
+    planted exact ties (duplicate retained vectors: the lowest position wins; zero vectors: slot 0), and the
+    averages must be the oracle's for the assignment the kernel took."""
+    g = torch.Generator().manual_seed(N + D + 7)
+    k = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    v = torch.randn((B, L, Hkv, N, D), generator=g).to(torch.bfloat16)
+    k *= (0.05 + 20.0 * torch.rand((B, L, Hkv, N, 1), generator=g)).to(torch.bfloat16)   # norms all over the place
+    imp = synthetic_importance(B, L, N, seed=N + 9)
+    budget = max(L + 1, int(frac * L * N))
+    sel = oracle.select(imp.numpy(), budget)
+    planted = []
+    for b in range(B):
+        for l in range(L):
+            n = int(sel["lengths"][b, l])
+            kept = np.sort(sel["order"][b, l, :n])
+            pruned = np.setdiff1d(np.arange(N), kept)
+            if n >= 4 and len(pruned) >= 3:
+                k[b, l, :, kept[n - 2]] = k[b, l, :, kept[1]]           # duplicate retained vectors
+                k[b, l, :, pruned[0]] = 2.0 * k[b, l, :, kept[1]]       # parallel to both: exact tie
+                v[b, l, :, pruned[1]] = 0.0                             # zero vector
+                v[b, l, :, kept[2]] = 0.0                               # zero retained vector
+                planted.append((b, l, pruned[0], 1, pruned[1]))
+    got, want = run_compact(k, v, sel, 2, budget)
+    match = P.prefixkv_merge_feature(got, k.to(DEV), v.to(DEV))
+    torch.cuda.synchronize()
+    gm = match.cpu().numpy()
+    for plane, name, src in ((0, "kc", np32(k)), (1, "vc", np32(v))):
+        wm, best = oracle.feature_match(want, src)
+        np.testing.assert_array_equal(gm[plane] == -1, wm == -1)
+        assert (gm[plane] >= -1).all()
+        for b in range(B):
+            for l in range(L):
+                assert (gm[plane, b, l] < max(1, int(sel["lengths"][b, l]))).all()
+        cos = oracle.match_cosine(want, src, gm[plane])
+        assert (cos >= best - 5e-6).all(), float((best - cos).max())
+        assert (gm[plane] != wm).mean() < 1e-3            # near ties are rare
+        oracle.merge_by_match(want, name, src, gm[plane], storage_bf16=True)
+    for b, l, m_dup, slot_dup, m_zero in planted:
+        assert (gm[0, b, l, :, m_dup] == slot_dup).all()
+        assert (gm[1, b, l, :, m_zero] == 0).all()
+    np.testing.assert_array_equal(got.lens.cpu().numpy(), want["lens"])
+    kc, vc = np32(got.kc), np32(got.vc)
+    for b in range(B):
+        for l in range(L):
+            off, cap, n = int(want["seg_off"][b, l]), int(want["caps"][b, l]), int(want["lens"][b, l])
+            gk = kc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
+            gv = vc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
+            # fp32 sums on the GPU, fp64 in the oracle: equal up to one unit in the last place of bf16
+            # (and up to the rounding of an fp32 sum where the terms cancel)
+            np.testing.assert_allclose(gk, oracle.segment(want, "kc", b, l)[:, :n], rtol=2.0 ** -7, atol=1e-4)
+            np.testing.assert_allclose(gv, oracle.segment(want, "vc", b, l)[:, :n], rtol=2.0 ** -7, atol=1e-4)
+    if frac == 1.0:
+        assert (gm == -1).all()
+
+
 @pytest.mark.parametrize("B,L,Hkv,N,D,dtype,frac", [
     (1, 4, 2, 128, 64, torch.float32, 0.5),
     (2, 3, 4, 333, 128, torch.bfloat16, 0.2),
