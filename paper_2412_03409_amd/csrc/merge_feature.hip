@@ -13,9 +13,9 @@
 //                      and 16 slots in ascending order, so the running (best score, slot) pair is per lane
 //                      and the two halves of a column meet once at the end.  |x_m| is a positive factor
 //                      common to all candidates of position m and is left out; score = dot * 1/|x_u|.
-//  mf_average_kernel   per (tensor, segment, kv head, part of the slot list): the assignment row sits in LDS;
-//                      a wavefront takes a slot, finds its members with one ballot per 64 positions and sums
-//                      their rows, 64/LPR rows per load, in a fixed order (fp32), then stores the mean.
+//  mf_average_kernel   per (tensor, segment, kv head): sorts the pruned positions by (slot, position) in LDS, so
+//                      that the members of a slot are one run; a wavefront sums the rows of a run, 64/LPR rows
+//                      per load and four loads deep, in a fixed order (fp32), then stores the mean.
 #include "pkv_common.hpp"
 
 namespace pkv {
@@ -34,7 +34,7 @@ struct MergeFeatureParams {
     const int64_t* seg_off; const int32_t* caps; const int32_t* kept_pos; const int32_t* lens;
     int32_t* match;             // [2][B*L*Hkv][N]
     float* inv_norm;            // [2][B*L*Hkv][NP]
-    int nparts;
+    int np2;                    // N rounded up to a power of two (>= 64): keys sorted by the averaging kernel
 };
 
 // chunk swizzle of the staged rows (16-byte chunk c of row r sits at c ^ swz(r)): the fragment reads touch
@@ -203,80 +203,133 @@ mf_match_kernel(MergeFeatureParams p) {
     }
 }
 
+// 8 bf16 of a row added to fp32 sums; the mean of 8 sums stored as bf16 (round to nearest even)
+__device__ __forceinline__ void add_row(float (&acc)[8], const uint4& w4) {
+    const uint32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        acc[2 * x] += __uint_as_float(w[x] << 16);
+        acc[2 * x + 1] += __uint_as_float(w[x] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void store_mean(bf16_t* dst, const float (&acc)[8], float cnt) {
+    uint32_t o[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+        o[x] = (uint32_t)f32_to_bf16(acc[2 * x] / cnt) | ((uint32_t)f32_to_bf16(acc[2 * x + 1] / cnt) << 16);
+    *(uint4*)dst = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// One workgroup per (tensor, segment, kv head).  The pruned positions are sorted by (slot, position) -- keys
+// slot << 13 | position, retained positions as the largest key, a bitonic network in LDS -- so that the members
+// of every slot are one contiguous, ascending run.  A wavefront then takes 64 slots at a time (each lane finds
+// the run of one slot by binary search); a row group (LPR lanes, 16 bytes of the row each) sums the run of one
+// slot in ascending order, four loads deep; a run longer than kLongRun is summed by all row groups of the
+// wavefront together, in a fixed order.
 template <int LPR>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(1024)
 mf_average_kernel(MergeFeatureParams p) {
     constexpr int RPI = kWave / LPR;             // rows per wavefront-wide load
-    __shared__ __attribute__((aligned(16))) int32_t sm[kMaxN];
+    constexpr int kDeep = 4;                     // loads in flight per row group
+    constexpr int kLongRun = 64;
+    extern __shared__ __attribute__((aligned(16))) uint32_t keys[];   // np2 keys
     const int U = p.U;
-    const int part = blockIdx.x % p.nparts, u = (blockIdx.x / p.nparts) % U, tz = blockIdx.x / (p.nparts * U);
+    const int u = blockIdx.x % U, tz = blockIdx.x / U;
     const int seg = u / p.Hkv, h = u % p.Hkv;
     const int n = p.lens[seg];
     if (n >= p.N || n < 1) return;               // nothing was pruned: the compacted rows stay as they are
-    const int per = (n + p.nparts - 1) / p.nparts;
-    const int j0 = part * per, j1 = min(n, j0 + per);
-    if (j0 >= j1) return;
     const int b = seg / p.L, l = seg % p.L;
     const int64_t off = p.seg_off[seg];
     const int32_t* kp = p.kept_pos + off;
     const Strides xs = p.xs[tz];
-    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave, nwv = blockDim.x / kWave;
     const int sub = lane % LPR, rg = lane / LPR;
     const bf16_t* xbase = p.x[tz] + xs.b * b + xs.l * l + xs.h * h + sub * 8;
     bf16_t* cbase = p.xc[tz] + ((size_t)off * p.Hkv + (size_t)h * p.caps[seg]) * (LPR * 8) + sub * 8;
     const int32_t* mrow = p.match + ((size_t)tz * U + u) * p.N;
-    const int n256 = (p.N + 255) & ~255;
-    for (int m = threadIdx.x; m < n256; m += blockDim.x) sm[m] = m < p.N ? mrow[m] : -1;
+    const int np2 = p.np2;
+    for (int m = threadIdx.x; m < np2; m += blockDim.x) {
+        const int slot = m < p.N ? mrow[m] : -1;
+        keys[m] = (slot >= 0 && slot < n) ? ((uint32_t)slot << 13) | (uint32_t)m : 0xffffffffu;
+    }
     __syncthreads();
-
-    for (int j = j0 + wv; j < j1; j += 4) {
-        float acc[8];
-#pragma unroll
-        for (int x = 0; x < 8; ++x) acc[x] = 0.f;
-        auto add_row = [&](int m) {
-            const uint4 w4 = *(const uint4*)(xbase + (uint32_t)m * (uint32_t)xs.n);
-            const uint32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                acc[2 * x] += __uint_as_float(w[x] << 16);
-                acc[2 * x + 1] += __uint_as_float(w[x] & 0xffff0000u);
+    for (int k = 2; k <= np2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < np2 / 2; t += blockDim.x) {
+                const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), q = i | j;
+                const uint32_t a = keys[i], c = keys[q];
+                if ((a > c) == ((i & k) == 0)) { keys[i] = c; keys[q] = a; }
             }
-        };
-        if (rg == 0) add_row(kp[j]);             // the retained vector itself
-        int cnt = 1;
-        for (int base = 0; base < n256; base += 256) {
-            const int4 v4 = *(const int4*)(sm + base + 4 * lane);
-            const int vv[4] = {v4.x, v4.y, v4.z, v4.w};
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                unsigned long long mask = __builtin_amdgcn_ballot_w64(vv[c] == j);
-                cnt += __builtin_popcountll(mask);
-                while (mask) {                   // RPI members at a time, one per row group
-                    int mine = -1;
-#pragma unroll
-                    for (int i = 0; i < RPI; ++i) {
-                        if (mask) {
-                            const int bit = __builtin_ctzll(mask);
-                            mask &= mask - 1;
-                            if (rg == i) mine = base + 4 * bit + c;
-                        }
-                    }
-                    if (mine >= 0) add_row(mine);
-                }
-            }
+            __syncthreads();
         }
-        // row groups in a fixed order
+
+    // slots per wavefront and turn: up to 64, fewer when that leaves wavefronts without work
+    const int bs = min(kWave, ((n + nwv - 1) / nwv + RPI - 1) / RPI * RPI);
+    for (int jb = wv * bs; jb < n; jb += nwv * bs) {
+        // lane s: the run of slot jb + s = [first key >= slot << 13, first key >= (slot + 1) << 13)
+        int lo_l, hi_l;
+        {
+            const uint32_t t0 = (uint32_t)(jb + lane) << 13, t1 = t0 + (1u << 13);
+            int lo = 0, hi = np2;
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (keys[mid] < t0) lo = mid + 1; else hi = mid; }
+            lo_l = lo;
+            hi = np2;
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (keys[mid] < t1) lo = mid + 1; else hi = mid; }
+            hi_l = lo;
+        }
+        const int ns = min(bs, n - jb);
+        const unsigned long long longmask = __builtin_amdgcn_ballot_w64(lane < ns && hi_l - lo_l > kLongRun);
+        // runs of ordinary length: one row group per slot, RPI slots of the wavefront at a time
+        for (int s0 = 0; s0 < ns; s0 += RPI) {
+            const int s = s0 + rg;               // < 64
+            const bool act = s < ns && !((longmask >> s) & 1ull);
+            // (both shuffles outside any condition: a lane that sits out must still serve as a source)
+            const int lo = __shfl(lo_l, s, kWave), hi_s = __shfl(hi_l, s, kWave);
+            const int hi = act ? hi_s : lo;
+            float acc[8];
 #pragma unroll
-        for (int sh = LPR; sh < kWave; sh <<= 1)
+            for (int x = 0; x < 8; ++x) acc[x] = 0.f;
+            uint4 own = make_uint4(0, 0, 0, 0);  // zero bits are 0.0
+            if (act) own = *(const uint4*)(xbase + (uint32_t)kp[jb + s] * (uint32_t)xs.n);   // the retained vector
+            for (int i0 = lo; i0 < hi; i0 += kDeep) {
+                uint4 r[kDeep];
 #pragma unroll
-            for (int x = 0; x < 8; ++x) acc[x] += __shfl_xor(acc[x], sh, kWave);
-        if (rg == 0) {
-            const float fc = (float)cnt;
-            uint32_t o[4];
+                for (int d = 0; d < kDeep; ++d) {
+                    r[d] = make_uint4(0, 0, 0, 0);
+                    if (i0 + d < hi) r[d] = *(const uint4*)(xbase + (keys[i0 + d] & 8191u) * (uint32_t)xs.n);
+                }
 #pragma unroll
-            for (int x = 0; x < 4; ++x)
-                o[x] = (uint32_t)f32_to_bf16(acc[2 * x] / fc) | ((uint32_t)f32_to_bf16(acc[2 * x + 1] / fc) << 16);
-            *(uint4*)(cbase + (size_t)j * (LPR * 8)) = make_uint4(o[0], o[1], o[2], o[3]);
+                for (int d = 0; d < kDeep; ++d) add_row(acc, r[d]);
+            }
+            add_row(acc, own);
+            if (act) store_mean(cbase + (size_t)(jb + s) * (LPR * 8), acc, (float)(hi - lo + 1));
+        }
+        // long runs (few retained vectors, or one that attracts everything): the whole wavefront per slot
+        for (unsigned long long lm = longmask; lm; lm &= lm - 1) {
+            const int s = __builtin_ctzll(lm);
+            const int lo = __shfl(lo_l, s, kWave), hi = __shfl(hi_l, s, kWave);
+            float acc[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) acc[x] = 0.f;
+            uint4 own = make_uint4(0, 0, 0, 0);
+            if (rg == 0) own = *(const uint4*)(xbase + (uint32_t)kp[jb + s] * (uint32_t)xs.n);
+            for (int i0 = lo; i0 < hi; i0 += kDeep * RPI) {
+                uint4 r[kDeep];
+#pragma unroll
+                for (int d = 0; d < kDeep; ++d) {
+                    const int i = i0 + d * RPI + rg;
+                    r[d] = make_uint4(0, 0, 0, 0);
+                    if (i < hi) r[d] = *(const uint4*)(xbase + (keys[i] & 8191u) * (uint32_t)xs.n);
+                }
+#pragma unroll
+                for (int d = 0; d < kDeep; ++d) add_row(acc, r[d]);
+            }
+            add_row(acc, own);
+#pragma unroll
+            for (int sh = LPR; sh < kWave; sh <<= 1)
+#pragma unroll
+                for (int x = 0; x < 8; ++x) acc[x] += __shfl_xor(acc[x], sh, kWave);
+            if (rg == 0) store_mean(cbase + (size_t)(jb + s) * (LPR * 8), acc, (float)(hi - lo + 1));
         }
     }
 }
@@ -298,19 +351,21 @@ hipError_t launch_merge_feature(const pkv_shape& s, const void* k, Strides ks, c
     p.match = match; p.inv_norm = (float*)ws;
     const int U = s.B * s.L * s.Hkv;
     p.U = U;
-    // enough workgroups to fill the chip a few times over, but never tiny ones
-    int nparts = (2048 + 2 * U - 1) / (2 * U);
-    p.nparts = nparts < 1 ? 1 : (nparts > 16 ? 16 : nparts);
+    int np2 = 64;
+    while (np2 < s.N) np2 <<= 1;
+    p.np2 = np2;
+    const int nt = np2 <= 2048 ? 256 : 1024;
+    const size_t lds = (size_t)np2 * sizeof(uint32_t);
     p.nmb = (s.N + kMfRows - 1) / kMfRows;
-    const dim3 g_prep(2u * U), g_match(2u * U * p.nmb), g_avg(2u * U * p.nparts);
+    const dim3 g_prep(2u * U), g_match(2u * U * p.nmb), g_avg(2u * U);
     if (s.D == 128) {
         hipLaunchKernelGGL(mf_prepare_kernel<16>, g_prep, dim3(256), 0, st, p);
         hipLaunchKernelGGL(mf_match_kernel<128>, g_match, dim3(256), 0, st, p);
-        hipLaunchKernelGGL(mf_average_kernel<16>, g_avg, dim3(256), 0, st, p);
+        hipLaunchKernelGGL(mf_average_kernel<16>, g_avg, dim3(nt), lds, st, p);
     } else {
         hipLaunchKernelGGL(mf_prepare_kernel<8>, g_prep, dim3(256), 0, st, p);
         hipLaunchKernelGGL(mf_match_kernel<64>, g_match, dim3(256), 0, st, p);
-        hipLaunchKernelGGL(mf_average_kernel<8>, g_avg, dim3(256), 0, st, p);
+        hipLaunchKernelGGL(mf_average_kernel<8>, g_avg, dim3(nt), lds, st, p);
     }
     return hipGetLastError();
 }
