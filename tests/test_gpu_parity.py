@@ -50,6 +50,8 @@ def check_importance(got, want):
     (1, 2, 2, 1, 31, 128, torch.bfloat16),     # less than one MFMA tile
     (1, 1, 3, 3, 680, 128, torch.bfloat16),    # the LLaVA prompt length
     (1, 1, 2, 2, 1100, 128, torch.bfloat16),   # beyond 1024
+    (1, 1, 2, 1, 2300, 128, torch.bfloat16),   # long prompt: the software-pipelined stages below the diagonal
+    (1, 1, 1, 1, 2100, 64, torch.bfloat16),    # ... with D = 64
 ])
 def test_importance_matches_oracle(B, L, H, Hkv, N, D, dtype):
     q, k, scale = rand_qk(N + D + H, B, L, H, Hkv, N, D, dtype)
