@@ -56,6 +56,10 @@ def main() -> int:
                     help="decode with pruning at distance D from the newest token instead of append-only")
     ap.add_argument("--no-graph", action="store_true", help="launch every decode step from Python")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the entry points beyond the core path (prefill attention, one-pass importance, "
+                         "ranking + offline configuration, Gini, positional and feature merging) and add them to "
+                         "the line as \"extras\"")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
                     help="only run the plain copy kernel on BYTES (for calibrating rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -181,6 +185,7 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(w, x, dec, hp, Bk)
+    extras = time_extras(P, w, x, hp, Bk, T) if args.extras else None
 
     line = {
         "metric": "compressed decode tok/s (attention over all layers per step) + prefixkv_select ms; "
@@ -194,8 +199,61 @@ def main() -> int:
         "prefixkv_select_ms": round(sel_ms, 4),
         "stages": extra, "roofline": roofline, "cpu_baseline": cpu,
     }
+    if extras is not None:
+        line["extras"] = extras
     print(json.dumps(line))
     return 0
+
+
+def time_extras(P, w, x, hp, Bk, T, reps=5):
+    """Average time (ms, HIP events on the current stream) of the entry points beyond the core path, on the
+    same resident inputs.  The two merges rewrite the compacted cache, so they come last."""
+    import torch
+    dev = x["q"].device
+
+    def ms(fn, n=reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    out = {}
+    flops1 = w.B * w.L * w.H * w.N * (w.N + 1) * w.D           # one causal product
+    if w.dtype == "bf16":
+        o = torch.empty_like(x["q"])
+        lse = torch.empty((w.B, w.L, w.H, w.N), dtype=torch.float32, device=dev)
+        t = ms(lambda: P.prefixkv_prefill_attn(x["q"], x["k"], x["v"], x["scale"], out=o, lse=lse))
+        out["prefill_attn"] = {"ms": round(t, 4), "tflops": round(2 * flops1 / t / 1e9, 1)}
+        t = ms(lambda: P.prefixkv_importance(x["q"], x["k"], x["scale"], lse=lse))
+        out["importance_with_lse"] = {"ms": round(t, 4), "tflops": round(flops1 / t / 1e9, 1), "passes": 1}
+        del o
+    rk = P.prefixkv_rank(hp.importance)
+    out["rank"] = {"ms": round(ms(lambda: P.prefixkv_rank(hp.importance, out=rk)), 4)}
+    samples = hp.sel.lengths[:1].repeat(10, 1).contiguous()      # ten calibration samples of this shape
+    cfg = P.prefixkv_offline_config(samples, w.N, Bk, w.B)
+    out["offline_config"] = {"ms": round(ms(lambda: P.prefixkv_offline_config(samples, w.N, Bk, w.B, out=cfg)), 4),
+                             "samples": 10}
+    g = P.prefixkv_gini(hp.sel.cum)
+    out["gini"] = {"ms": round(ms(lambda: P.prefixkv_gini(hp.sel.cum, out=g)), 4),
+                   "min": round(float(g.min()), 4), "max": round(float(g.max()), 4)}
+    hp.run_compact()
+    rows = 2 * w.B * w.L * w.Hkv * w.N * w.D * w.elem_bytes      # every row of K and V is read once
+    t = ms(lambda: P.prefixkv_merge_position(hp.cache, x["k"], x["v"]))
+    out["merge_position"] = {"ms": round(t, 4), "GBps_rows_read": round(rows / t / 1e6, 1)}
+    if w.dtype == "bf16":
+        hp.run_compact()
+        match = torch.empty((2, w.B, w.L, w.Hkv, w.N), dtype=torch.int32, device=dev)
+        need = P.prefixkv_workspace_bytes(P.binding.OP_MERGE_FEATURE, w.B, w.L, w.H, w.Hkv, w.N, w.D, P.PKV_BF16)
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+        t = ms(lambda: P.prefixkv_merge_feature(hp.cache, x["k"], x["v"], match=match, ws=ws), 3)
+        mflops = 2.0 * 2 * w.Hkv * w.D * w.N * float(hp.sel.lengths.sum())
+        out["merge_feature"] = {"ms": round(t, 4), "matching_tflops_overall": round(mflops / t / 1e9, 1)}
+    return out
 
 
 def cpu_baseline(w, x, dec, hp, Bk):
