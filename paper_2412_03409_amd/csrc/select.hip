@@ -3,7 +3,7 @@
 //  sort_prefix_kernel  one workgroup per (sequence, layer): the priority sequence of Sec. 3.2 (positions
 //                      by importance, descending) by a bitonic sort of 64-bit keys held in LDS, then the
 //                      cumulative priority as an exact integer scan of fixed-point weights.
-//  search_kernel       one wavefront per sequence, one lane per layer: Algorithm 1 (Sec. 3.3) runs to
+//  search_kernel       one workgroup per sequence, 32 lanes per layer: Algorithm 1 (Sec. 3.3) runs to
 //                      completion on the device, followed by the proportional rescale to the budget.
 //
 // Everything that decides an index or a length is integer or a single fp64 product + compare, so the
@@ -26,6 +26,13 @@ __device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int d) {
     uint32_t lo = __shfl_up((uint32_t)v, d, kWave);
     uint32_t hi = __shfl_up((uint32_t)(v >> 32), d, kWave);
     return ((uint64_t)hi << 32) | lo;
+}
+
+// LDS written by lanes of one wavefront becomes visible to the other lanes of the same wavefront
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // Sort key: high word = ~bits(importance) (non-negative floats order like their bit patterns, so the
@@ -68,7 +75,11 @@ __global__ void sort_prefix_kernel(int N, int P, const float* __restrict__ impor
                 const bool up = (i & k) == 0;
                 if ((a > b) == up) { skey[i] = b; skey[x] = a; }
             }
-            __syncthreads();
+            // A wavefront's 64 pairs of a stage with partner distance j <= 64 lie in one aligned block of
+            // 128 keys, the same block for all such stages: only a stage that reaches further (or is
+            // followed by one that does) has to meet the other wavefronts.
+            const int jn = j > 1 ? (j >> 1) : k;          // partner distance of the next stage
+            if (j > kWave || jn > kWave) __syncthreads(); else wave_sync();
         }
     }
 
@@ -153,9 +164,9 @@ __device__ __forceinline__ void rescale_wave(int L, int N, uint64_t weight, uint
                                  : (rj < rem || (rj == rem && j < lane));
         rank += before ? 1 : 0;
     }
-    __syncthreads();
+    wave_sync();
     if (act) { s_sorted[rank] = lane; s_len[lane] = (int)bs; }
-    __syncthreads();
+    wave_sync();
     if (lane == 0 && dlt != 0) {
         int64_t left = grow ? dlt : -dlt;
         while (left > 0) {
@@ -184,74 +195,166 @@ __device__ __forceinline__ void rescale_wave(int L, int N, uint64_t weight, uint
             }
         }
     }
-    __syncthreads();
+    wave_sync();
     const int res = act ? s_len[lane] : 0;
-    __syncthreads();
+    wave_sync();
     if (act) out[lane] = res;
 }
 
-// One wavefront per sequence.  Lane l owns layer l (l < L <= 64); p1, p2, p live in every lane with
-// identical arithmetic, so control flow stays uniform and no iteration leaves the device.
-__global__ void __launch_bounds__(kWave)
+// Algorithm 1 (Sec. 3.3) for one sequence per workgroup.  A group of 32 lanes owns a layer (two layers when
+// L > 32); p1, p2, p live in every thread with identical arithmetic, so control flow stays uniform and no
+// iteration leaves the device.  The prefix length of a layer at ratio p is the smallest k with C_k >= p*T
+// inside the bracket [k_lo, k_hi] left by the earlier iterations (the length is monotone in p).  Because the
+// cumulative sums ascend, any search order gives that same k; a group finds it 32 entries at a time instead of
+// one: 32 probes spread over the whole row are read once and kept in registers (they narrow every later
+// threshold to 1/33 of the row without a load), wider remainders are probed again, and the last 32 candidates
+// are held as a window that is reused as long as the bracket stays inside it.  Per iteration this costs one
+// dependent load or none, instead of log2(bracket).
+constexpr int kSearchGroup = 32;
+constexpr int kSearchThreads = 1024;
+
+struct LayerSearch {
+    const uint64_t* c;       // c[k-1] = C_k
+    int k_lo, k_hi, k;
+    int cstep_w;             // N - 1 when the coarse probes exist, else 0
+    uint64_t cval;           // coarse probe of this lane: C at 1 + ((j+1) * (N-1)) / 33
+    int wbase;               // window: lane j holds C_{wbase + j}; wbase = 0: empty
+    uint64_t wval;
+};
+
+__device__ __forceinline__ uint32_t ballot32(bool pred, int lane) {
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(pred);
+    return (uint32_t)(m >> (lane & 32));
+}
+
+// smallest k in [k_lo, k_hi) with (double)C_k >= thr, k_hi if there is none; uniform within the 32-lane group
+__device__ __forceinline__ int search_layer(LayerSearch& s, double thr, int N, int lane) {
+    const int j = lane & 31;
+    int a = s.k_lo, e = s.k_hi;
+    if (s.cstep_w) {
+        const int kc = 1 + ((j + 1) * s.cstep_w) / 33;
+        const bool in = kc >= a && kc < e, ge = (double)s.cval >= thr;
+        const uint32_t m_ge = ballot32(in && ge, lane), m_lt = ballot32(in && !ge, lane);
+        if (m_ge) e = 1 + ((__builtin_ctz(m_ge) + 1) * s.cstep_w) / 33;
+        if (m_lt) a = 2 + ((32 - __builtin_clz(m_lt)) * s.cstep_w) / 33;
+    }
+    while (e - a > kSearchGroup) {
+        const int width = e - a;
+        const int kj = a + ((j + 1) * width) / 33;                  // a < kj < e, ascending in j
+        const bool ge = (double)s.c[kj - 1] >= thr;
+        const uint32_t m_ge = ballot32(ge, lane);
+        if (m_ge == 0) {
+            a = a + (32 * width) / 33 + 1;
+        } else {
+            const int js = __builtin_ctz(m_ge);
+            e = a + ((js + 1) * width) / 33;
+            if (js > 0) a = a + (js * width) / 33 + 1;
+        }
+    }
+    if (a < e) {
+        if (s.wbase == 0 || a < s.wbase || e > s.wbase + kSearchGroup) {
+            // anchor the window at the bracket when it already fits: every later search stays inside it
+            s.wbase = s.k_hi - s.k_lo <= kSearchGroup ? s.k_lo : a;
+            s.wval = s.wbase + j <= N ? s.c[s.wbase + j - 1] : ~0ull;
+        }
+        const int kk = s.wbase + j;
+        const uint32_t m = ballot32(kk >= a && kk < e && (double)s.wval >= thr, lane);
+        if (m) e = s.wbase + __builtin_ctz(m);
+    }
+    return e;
+}
+
+__global__ void __launch_bounds__(kSearchThreads)
 search_kernel(int L, int N, const uint64_t* __restrict__ cum, const int32_t* __restrict__ seg_status,
               int64_t budget, int64_t tol, int max_iters, int fixup, int32_t* __restrict__ lengths,
               double* __restrict__ p_out, int32_t* __restrict__ iters_out,
               int64_t* __restrict__ raw_total_out, int32_t* __restrict__ status) {
     __shared__ int s_sorted[kMaxL];
     __shared__ int s_len[kMaxL];
-    const int b = blockIdx.x, lane = threadIdx.x;
-    const bool act = lane < L;
-    const uint64_t* c = cum + ((size_t)b * L + (act ? lane : 0)) * (size_t)N;  // c[k-1] = C_k
+    __shared__ int s_k[2][kMaxL];
+    __shared__ int s_sum[3];     // total length of iteration it in s_sum[it % 3]
+    __shared__ int s_st;
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int grp = tid / kSearchGroup, ngrp = blockDim.x / kSearchGroup;
 
-    int st = act ? seg_status[(size_t)b * L + lane] : 0;
-    for (int d = 32; d > 0; d >>= 1) st |= __shfl_xor(st, d, kWave);
+    if (tid == 0) { s_st = 0; s_sum[0] = 0; s_sum[1] = 0; s_sum[2] = 0; }
+    __syncthreads();
+    if (tid < L && seg_status[(size_t)b * L + tid]) atomicOr(&s_st, seg_status[(size_t)b * L + tid]);
+    __syncthreads();
+    const int st = s_st;
     if (st) {
-        if (act) lengths[(size_t)b * L + lane] = 0;
-        if (lane == 0) { p_out[b] = 0.0; iters_out[b] = 0; raw_total_out[b] = 0; status[b] = st; }
+        if (tid < L) lengths[(size_t)b * L + tid] = 0;
+        if (tid == 0) { p_out[b] = 0.0; iters_out[b] = 0; raw_total_out[b] = 0; status[b] = st; }
         return;
     }
     if (budget <= L || budget >= (int64_t)L * N) {
         const bool all = budget > L;
-        if (act) lengths[(size_t)b * L + lane] = all ? N : 1;
-        if (lane == 0) {
+        if (tid < L) lengths[(size_t)b * L + tid] = all ? N : 1;
+        if (tid == 0) {
             p_out[b] = all ? 1.0 : 0.0; iters_out[b] = 0;
             raw_total_out[b] = all ? (int64_t)L * N : L; status[b] = 0;
         }
         return;
     }
 
-    const double T = act ? (double)c[N - 1] : 0.0;
-    // prefix lengths at the interval ends: k(p1 = 0) = 1, k(p2 = 1) = N.  The length is monotone in p,
-    // so the length at any midpoint lies between the lengths at the ends of the current interval.
-    int k_lo = 1, k_hi = N, k = 1;
+    // the layers of this group: grp and grp + ngrp (ngrp >= min(L, 32), L <= 64)
+    LayerSearch ls[2];
+    double T[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int l = grp + i * ngrp;
+        const bool act = l < L;
+        ls[i].c = cum + ((size_t)b * L + (act ? l : 0)) * (size_t)N;
+        ls[i].k_lo = 1; ls[i].k_hi = N; ls[i].k = 1; ls[i].wbase = 0; ls[i].wval = 0;
+        ls[i].cstep_w = N - 1 > kSearchGroup ? N - 1 : 0;
+        ls[i].cval = 0;
+        T[i] = 0.0;
+        if (act) {
+            T[i] = (double)ls[i].c[N - 1];
+            if (ls[i].cstep_w) ls[i].cval = ls[i].c[((lane & 31) + 1) * ls[i].cstep_w / 33];   // C at 1 + that
+        }
+    }
     double p1 = 0.0, p2 = 1.0, p = 0.5;
     int iters = 0, K = 0;
     for (int it = 1; it <= max_iters; ++it) {
         const double mid = 0.5 * (p1 + p2);
         if (mid == p1 || mid == p2) break;
         p = mid;
-        const double thr = __dmul_rn(p, T);  // one rounded product, never contracted
-        int a = k_lo, e = k_hi;              // smallest k in [a, e] with C_k >= thr (k = e if none below)
-        while (a < e) {
-            const int m = (a + e) >> 1;
-            if ((double)c[m - 1] >= thr) e = m; else a = m + 1;
+        int* sk = s_k[it & 1];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int l = grp + i * ngrp;
+            if (l < L) {                                  // uniform within the group
+                const double thr = __dmul_rn(p, T[i]);    // one rounded product, never contracted
+                ls[i].k = search_layer(ls[i], thr, N, lane);
+                if ((lane & 31) == 0) { sk[l] = ls[i].k; atomicAdd(&s_sum[it % 3], ls[i].k); }
+            }
         }
-        k = a;
-        int sum = act ? k : 0;
-        for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, kWave);
-        K = sum;
+        __syncthreads();
+        K = s_sum[it % 3];
+        if (tid == 0) s_sum[(it + 2) % 3] = 0;            // next used two iterations from now, after another barrier
         iters = it;
         const int64_t delta = (int64_t)K - budget;
         if ((delta < 0 ? -delta : delta) <= tol) break;
-        if (delta < 0) { p1 = p; k_lo = k; } else { p2 = p; k_hi = k; }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (delta < 0) ls[i].k_lo = ls[i].k; else ls[i].k_hi = ls[i].k;
+        }
+        if (delta < 0) p1 = p; else p2 = p;
     }
-    if (lane == 0) { p_out[b] = p; iters_out[b] = iters; raw_total_out[b] = K; status[b] = 0; }
-
-    if (!fixup || K == budget) {
-        if (act) lengths[(size_t)b * L + lane] = k;
+    if (tid == 0) { p_out[b] = p; iters_out[b] = iters; raw_total_out[b] = K; status[b] = 0; }
+    if (iters == 0) {                                     // max_iters < 1 cannot happen (checked by the caller)
+        if (tid < L) lengths[(size_t)b * L + tid] = 1;
         return;
     }
-    rescale_wave(L, N, act ? (uint64_t)k : 0, (uint64_t)K, budget, lengths + (size_t)b * L, s_sorted, s_len);
+    // s_k[iters & 1] holds the lengths of the last iteration; every thread has passed its barrier
+    const int k_mine = tid < L ? s_k[iters & 1][tid] : 0;
+    if (!fixup || K == budget) {
+        if (tid < L) lengths[(size_t)b * L + tid] = k_mine;
+        return;
+    }
+    if (tid < kWave)                                      // one wavefront, lane l = layer l
+        rescale_wave(L, N, tid < L ? (uint64_t)k_mine : 0, (uint64_t)K, budget, lengths + (size_t)b * L, s_sorted, s_len);
 }
 
 // Offline configuration (Sec. 3.3, last paragraph): the lengths of S calibration sequences are summed per
@@ -343,7 +446,10 @@ hipError_t launch_select(int B, int L, int N, const float* importance, const pkv
                        prefix, seg_status);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(search_kernel, dim3(B), dim3(kWave), 0, st, L, N, cum, seg_status,
+    // one 32-lane group per layer (two layers per group beyond 32), whole wavefronts
+    int search_threads = (L * kSearchGroup + kWave - 1) / kWave * kWave;
+    if (search_threads > kSearchThreads) search_threads = kSearchThreads;
+    hipLaunchKernelGGL(search_kernel, dim3(B), dim3(search_threads), 0, st, L, N, cum, seg_status,
                        (int64_t)pr.budget_tokens, (int64_t)pr.tol_tokens, (int)pr.max_iters, (int)pr.fixup,
                        lengths, p_out, iters, raw_total, status);
     return hipGetLastError();

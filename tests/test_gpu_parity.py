@@ -104,7 +104,8 @@ def check_select(imp, budget, tol=0, max_iters=64, fixup=True):
 
 
 @pytest.mark.parametrize("B,L,N", [(1, 1, 1), (1, 3, 5), (2, 4, 128), (3, 32, 680), (2, 40, 680),
-                                   (1, 64, 64), (2, 8, 8192), (1, 5, 1025), (2, 7, 2049)])
+                                   (1, 64, 64), (2, 8, 8192), (1, 5, 1025), (2, 7, 2049),
+                                   (1, 2, 33), (2, 3, 34), (1, 33, 100), (1, 6, 1100)])   # probe / window boundaries
 @pytest.mark.parametrize("ties", [False, True])
 def test_select_bit_exact(B, L, N, ties):
     imp = synthetic_importance(B, L, N, seed=B * 1000 + L * 10 + N, ties=ties)
