@@ -434,7 +434,8 @@ __global__ void __launch_bounds__(kPlanThreads)
 decode_plan_kernel(DecodeParams p) {
     __shared__ int s_red[kPlanThreads];
     const int tid = threadIdx.x, n = p.n_seg;
-    const int per = (n + kPlanThreads - 1) / kPlanThreads;
+    const int nt = blockDim.x;               // a power of two, 64 .. kPlanThreads: no more wavefronts than the segments need
+    const int per = (n + nt - 1) / nt;
     const int lo = tid * per < n ? tid * per : n, hi = lo + per < n ? lo + per : n;
     int* hdr = p.plan;
     int* arrive = p.plan + kPlanHdr;
@@ -452,7 +453,7 @@ decode_plan_kernel(DecodeParams p) {
         }
         s_red[tid] = mine;
         __syncthreads();
-        for (int st = kPlanThreads / 2; st > 0; st >>= 1) {
+        for (int st = nt / 2; st > 0; st >>= 1) {
             if (tid < st) s_red[tid] += s_red[tid + st];
             __syncthreads();
         }
@@ -464,7 +465,7 @@ decode_plan_kernel(DecodeParams p) {
     // exclusive scan of the per-thread counts
     s_red[tid] = mine;
     __syncthreads();
-    for (int st = 1; st < kPlanThreads; st <<= 1) {
+    for (int st = 1; st < nt; st <<= 1) {
         const int v = tid >= st ? s_red[tid - st] : 0;
         __syncthreads();
         s_red[tid] += v;
@@ -509,7 +510,7 @@ decode_plan_kernel(DecodeParams p) {
         }
     }
     const int HU = p.H / p.G;
-    for (int i = tid; i < n * HU; i += kPlanThreads) arrive[i] = 0;
+    for (int i = tid; i < n * HU; i += nt) arrive[i] = 0;
     if (tid == 0) { hdr[0] = 0; hdr[1] = ok ? total * HU : 0; hdr[2] = S; hdr[3] = ok ? total : 0; hdr[4] = total_full; }
 }
 
@@ -886,7 +887,9 @@ static hipError_t launch_gqa_s(DecodeParams p, const pkv_shape& s, int* ws, hipS
     const GqaLayout lay = gqa_layout(s.B * p.nl, s.H, G, D, s.N);
     p.G = G; p.n_seg = s.B * p.nl; p.S0 = 1024; p.pieces_cap = lay.pieces_cap; p.record_word = lay.record_word; p.partial_word = lay.partial_word;
     p.plan = ws;
-    hipLaunchKernelGGL((decode_plan_kernel<EV>), dim3(1), dim3(kPlanThreads), 0, st, p);
+    int plan_threads = kWave;
+    while (plan_threads < p.n_seg && plan_threads < kPlanThreads) plan_threads <<= 1;
+    hipLaunchKernelGGL((decode_plan_kernel<EV>), dim3(1), dim3(plan_threads), 0, st, p);
     int grid = compute_units() * (8 / W);
     const long long most = (long long)lay.pieces_cap * (s.H / G);
     if (grid > most) grid = (int)most;
