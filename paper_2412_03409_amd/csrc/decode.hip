@@ -1,5 +1,6 @@
 // Stage 4b: one decode step over the ragged compressed cache (Sec. 3.1: the newest token's query
-// interacts with the cached KV vectors of every layer).  ONE kernel per step:
+// interacts with the cached KV vectors of every layer).  ONE kernel per step (two for bf16 caches whose
+// KV heads serve several query heads: a planning kernel and decode_gqa_kernel, further down):
 //
 //  decode_attn_kernel   a workgroup of a few wavefronts owns one (sequence, layer, kv head) -- or a
 //                       sub-group of G of its query heads -- and its wavefronts take the segment's
@@ -514,7 +515,8 @@ decode_plan_kernel(DecodeParams p) {
     if (tid == 0) { hdr[0] = 0; hdr[1] = ok ? total * HU : 0; hdr[2] = S; hdr[3] = ok ? total : 0; hdr[4] = total_full; }
 }
 
-// Persistent kernel: as many workgroups as fit on the chip, each taking every gridDim-th item of the list.
+// Persistent kernel: as many workgroups as fit on the chip; a workgroup starts with the item of its own
+// index and claims further items of the list from a counter.
 template <int D, int G, int NT, int W, int OCC, bool EV>
 __global__ void __launch_bounds__(W * kWave, OCC)
 decode_gqa_kernel(DecodeParams p) {
