@@ -220,3 +220,49 @@ def test_prefill_attention_feeds_one_pass_importance_at_full_size(name, layers):
             m_lo = w.N - 96
             want = oracle.importance(f32(x["q"][:1, sl]), f32(x["k"][:1, sl]), scale[sl], m_lo=m_lo)
             check_importance(imp1[:1, sl, m_lo:].cpu().numpy(), want[..., m_lo:])
+
+
+@pytest.mark.parametrize("name,layers", [("llava7b_b1", [0, 13, 31]), ("llava13b_b8", [7])])
+def test_merging_at_full_size(name, layers):
+    """Positional and feature merging at benchmark shapes, whole batch on the GPU; sampled layers of sequence 0
+    against the oracle.  Properties over everything: the assignment planes mark exactly the kept positions with
+    -1 and name slots below the layer's length elsewhere."""
+    w = CONFIGS[name]
+    Bk = w.budget_tokens(w.budget)
+    x = make_prefill(w, device=DEV)
+    hp = HotPath(x["q"], x["k"], x["v"], x["scale"], Bk, 2)
+    hp.run_importance(); hp.run_select(); hp.run_compact()
+    match = P.prefixkv_merge_feature(hp.cache, x["k"], x["v"])
+    torch.cuda.synchronize()
+    lens = hp.cache.lens.cpu().numpy()
+    gm = match.cpu().numpy()
+    assert ((gm == -1).sum(-1) == lens[None, :, :, None]).all()
+    assert (gm < lens[None, :, :, None, None]).all() and (gm >= -1).all()
+    kc_feat, vc_feat = hp.cache.kc.clone(), hp.cache.vc.clone()
+    hp.run_compact()
+    P.prefixkv_merge_position(hp.cache, x["k"], x["v"])
+    torch.cuda.synchronize()
+    sel_order, sel_len = hp.sel.order[:1].cpu().numpy(), hp.sel.lengths[:1].cpu().numpy()
+    seg_off, caps = hp.cache.seg_off.cpu().numpy(), hp.cache.caps.cpu().numpy()
+    Hkv, D = w.Hkv, w.D
+    for l in layers:
+        sl = slice(l, l + 1)
+        k1, v1 = f32(x["k"][:1, sl]), f32(x["v"][:1, sl])
+        n = int(sel_len[0, l])
+        off, cap = int(seg_off[0, l]), int(caps[0, l])
+        seg = lambda t: f32(t[off * Hkv * D:(off + cap) * Hkv * D]).reshape(Hkv, cap, D)[:, :n]
+        # feature merging: the kernel's choice is as good as the oracle's; averages for that choice
+        want = oracle.compact(k1, v1, sel_order[:, sl], sel_len[:, sl], 2)
+        for plane, nm, src, got in ((0, "kc", k1, kc_feat), (1, "vc", v1, vc_feat)):
+            wm, best = oracle.feature_match(want, src)
+            g = gm[plane, :1, sl]
+            np.testing.assert_array_equal(g == -1, wm == -1)
+            assert (oracle.match_cosine(want, src, g) >= best - 5e-6).all()
+            assert (g != wm).mean() < 1e-3
+            oracle.merge_by_match(want, nm, src, g, storage_bf16=True)
+            np.testing.assert_allclose(seg(got), oracle.segment(want, nm, 0, 0)[:, :n], rtol=2.0 ** -7, atol=1e-4)
+        # positional merging
+        want = oracle.compact(k1, v1, sel_order[:, sl], sel_len[:, sl], 2)
+        oracle.merge_position(want, k1, v1, storage_bf16=True)
+        np.testing.assert_allclose(seg(hp.cache.kc), oracle.segment(want, "kc", 0, 0)[:, :n], rtol=2.0 ** -7, atol=1e-4)
+        np.testing.assert_allclose(seg(hp.cache.vc), oracle.segment(want, "vc", 0, 0)[:, :n], rtol=2.0 ** -7, atol=1e-4)
