@@ -432,8 +432,17 @@ __global__ void head_mean_kernel(int H, int N, long long total, const float* __r
     if (i >= total) return;
     const long long bl = i / N;
     const int n = (int)(i % N);
+    const float* src = partial + (size_t)bl * H * N + n;
     float acc = 0.f;
-    for (int h = 0; h < H; ++h) acc += partial[((size_t)bl * H + h) * N + n];
+    int h = 0;
+    for (; h + 8 <= H; h += 8) {             // eight loads in flight, added in head order
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = src[(size_t)(h + j) * N];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc += v[j];
+    }
+    for (; h < H; ++h) acc += src[(size_t)h * N];
     importance[i] = acc / (float)H;
 }
 
