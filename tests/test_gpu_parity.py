@@ -461,6 +461,11 @@ def run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed, layer_range=No
     (1, 2, 16, 2, 2500, 64, torch.bfloat16, 0.95, 2),   # grouped (8 heads), D = 64, split segments
     (2, 3, 8, 2, 1100, 128, torch.bfloat16, 0.95, 3),   # the appended row crosses a piece boundary (1024)
     (1, 1, 8, 1, 8192, 128, torch.bfloat16, 1.0, 1),    # grouped (8 heads), one segment of 8 pieces
+    # 512 to 1024 (sequence, layer, head) units: the largest launches that are resident at once
+    (2, 9, 32, 32, 70, 64, torch.bfloat16, 0.3, 3),
+    (3, 6, 32, 32, 200, 128, torch.bfloat16, 0.5, 2),
+    (1, 18, 32, 32, 50, 64, torch.float32, 0.4, 2),
+    (1, 5, 120, 120, 40, 64, torch.bfloat16, 1.0, 2),   # many heads, full budget
 ])
 def test_decode_matches_oracle(B, L, H, Hkv, N, D, dtype, frac, steps):
     run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed=N + H)
@@ -572,6 +577,8 @@ def test_decode_layer_range_and_rejected_sequence():
     run_decode_case(2, 4, 4, 4, 100, 128, torch.bfloat16, 0.3, 2, seed=7, layer_range=(1, 3))
     run_decode_case(2, 4, 8, 2, 1300, 128, torch.bfloat16, 0.9, 2, seed=9, layer_range=(1, 3))   # grouped, split
     run_decode_case(2, 3, 4, 2, 100, 128, torch.bfloat16, 0.3, 2, seed=8, zero_seq=True)
+    run_decode_case(2, 12, 32, 32, 60, 64, torch.bfloat16, 0.4, 2, seed=10, layer_range=(2, 11))   # many units, layer range
+    run_decode_case(2, 10, 32, 32, 60, 64, torch.bfloat16, 0.4, 2, seed=11, zero_seq=True)         # many units, one empty sequence
 
 
 def test_full_budget_reproduces_full_cache_attention():
