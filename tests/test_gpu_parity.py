@@ -120,6 +120,22 @@ def test_select_bit_exact(B, L, N, ties):
     check_select(imp, max(L + 1, total // 2), tol=3, fixup=False)
 
 
+def test_select_random_shapes():
+    """Seeded random shapes, budgets, tolerances and iteration limits: everything stage 2+3 returns is bit-exact."""
+    r = np.random.default_rng(2024)
+    for case in range(80):
+        B, L = int(r.integers(1, 4)), int(r.integers(1, 65))
+        N = int(r.choice([1, 2, 7, 31, 32, 33, 34, 35, 63, 64, 65, 100, 257, 680, 1023, 1024, 1025, 1089, 1090, 1200, 3000]))
+        imp = synthetic_importance(B, L, N, seed=1000 + case, ties=bool(case % 3 == 0))
+        if case % 7 == 0 and N > 4:
+            imp[:, :, N // 2:] = 0.0                     # long runs of zero weight: flat cumulative sums
+        total = L * N
+        budget = int(r.integers(1, total + 3))
+        tol = int(r.choice([0, 0, 1, 5, max(1, N // 10)]))
+        max_iters = int(r.choice([1, 2, 3, 8, 64]))
+        check_select(imp, budget, tol=tol, max_iters=max_iters, fixup=bool(case % 2))
+
+
 def test_select_identical_layers_need_the_rescale():
     # all layers jump together, so most totals are unreachable: exercises stall + largest remainder
     row = synthetic_importance(1, 1, 96, seed=3)[0, 0]
@@ -471,6 +487,27 @@ def test_decode_matches_oracle(B, L, H, Hkv, N, D, dtype, frac, steps):
     run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed=N + H)
 
 
+def test_decode_random_shapes():
+    """Seeded random shapes over every launch path: one head per workgroup, fp32 head groups, the grouped-query
+    kernel with and without split segments, layer ranges, one to three steps."""
+    r = np.random.default_rng(77)
+    for case in range(36):
+        B, L = int(r.integers(1, 4)), int(r.integers(1, 6))
+        Hkv = int(r.choice([1, 2, 4]))
+        grp = int(r.choice([1, 1, 2, 3, 4, 8]))
+        D = int(r.choice([64, 128]))
+        dtype = torch.float32 if case % 5 == 4 else torch.bfloat16
+        N = int(r.choice([1, 5, 63, 64, 65, 130, 300, 700, 1100, 2300]))
+        if dtype == torch.float32 and N > 700:
+            N = 700
+        frac = float(r.choice([0.05, 0.2, 0.5, 0.9, 1.0]))
+        steps = int(r.integers(1, 4))
+        l0 = int(r.integers(0, L))
+        l1 = int(r.integers(l0 + 1, L + 1))
+        run_decode_case(B, L, Hkv * grp, Hkv, N, D, dtype, frac, steps, seed=500 + case,
+                        layer_range=(l0, l1) if case % 2 else None)
+
+
 # ------------------------------------------------ decode with pruning at a fixed distance (Sec. 3.1)
 def run_evict_case(B, L, H, Hkv, N, D, dtype, frac, d, steps, seed, extra=None, zero_seq=False):
     g = torch.Generator().manual_seed(seed)
@@ -533,6 +570,24 @@ def run_evict_case(B, L, H, Hkv, N, D, dtype, frac, d, steps, seed, extra=None, 
 ])
 def test_decode_evict_matches_oracle(B, L, H, Hkv, N, D, dtype, frac, d, steps):
     run_evict_case(B, L, H, Hkv, N, D, dtype, frac, d, steps, seed=N + H + d)
+
+
+def test_decode_evict_random_shapes():
+    """Seeded random shapes, distances and step counts for decode with pruning (all launch paths)."""
+    r = np.random.default_rng(78)
+    for case in range(20):
+        B, L = int(r.integers(1, 3)), int(r.integers(1, 5))
+        Hkv = int(r.choice([1, 2, 4]))
+        grp = int(r.choice([1, 1, 2, 4, 8]))
+        D = int(r.choice([64, 128]))
+        dtype = torch.float32 if case % 6 == 5 else torch.bfloat16
+        N = int(r.choice([5, 40, 64, 130, 300, 1100]))
+        if dtype == torch.float32 and N > 300:
+            N = 300
+        frac = float(r.choice([0.1, 0.3, 0.6, 1.0]))
+        d = int(r.choice([1, 2, 3, 5, 9, 40]))
+        steps = int(r.integers(1, 13))
+        run_evict_case(B, L, Hkv * grp, Hkv, N, D, dtype, frac, d, steps, seed=900 + case)
 
 
 def test_decode_evict_rejected_sequence_and_size_law():
