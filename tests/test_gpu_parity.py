@@ -65,6 +65,38 @@ def test_importance_matches_oracle(B, L, H, Hkv, N, D, dtype):
     check_importance(np32(got2), want)
 
 
+def test_importance_and_prefill_random_shapes():
+    """Seeded random shapes (prompt lengths around every tile, block and stage boundary, both head dimensions,
+    grouped heads, negative scales): importance in one and two passes, and for bf16 the prefill attention."""
+    r = np.random.default_rng(79)
+    for case in range(18):
+        B, L = int(r.integers(1, 3)), int(r.integers(1, 4))
+        Hkv = int(r.choice([1, 2, 3]))
+        grp = int(r.choice([1, 1, 2, 4]))
+        D = int(r.choice([64, 128]))
+        dtype = torch.float32 if case % 6 == 5 else torch.bfloat16
+        N = int(r.choice([2, 17, 32, 33, 64, 127, 128, 129, 255, 256, 257, 384, 511, 513, 640, 769, 1025]))
+        if dtype == torch.float32 and N > 300:
+            N = 129
+        q, k, scale = rand_qk(3000 + case, B, L, Hkv * grp, Hkv, N, D, dtype)
+        if case % 4 == 3:
+            scale = -scale
+        want, lse = oracle.importance(np32(q), np32(k), scale.numpy(), want_lse=True)
+        got = P.prefixkv_importance(q.to(DEV), k.to(DEV), scale.to(DEV))
+        check_importance(np32(got), want)
+        got2 = P.prefixkv_importance(q.to(DEV), k.to(DEV), scale.to(DEV),
+                                     lse=torch.from_numpy(lse.astype(np.float32)).to(DEV))
+        check_importance(np32(got2), want)
+        if dtype == torch.bfloat16:
+            g = torch.Generator().manual_seed(4000 + case)
+            v = torch.randn(k.shape, generator=g).to(torch.bfloat16)
+            out, lse_g = P.prefixkv_prefill_attn(q.to(DEV), k.to(DEV), v.to(DEV), scale.to(DEV))
+            want_out, want_lse = oracle.prefill_attn(np32(q), np32(k), np32(v), scale.numpy(), out_bf16=True)
+            torch.cuda.synchronize()
+            assert np.abs(np32(out) - want_out).max() <= OUT_ATOL, case
+            np.testing.assert_allclose(lse_g.cpu().numpy(), want_lse, rtol=1e-4, atol=3e-4)
+
+
 def test_importance_strided_inputs_and_determinism():
     B, L, H, N, D = 1, 2, 4, 150, 128
     q, k, scale = rand_qk(5, B, L, H, H, N, D, torch.bfloat16)
@@ -366,6 +398,53 @@ def test_compact_bit_exact(B, L, Hkv, N, D, dtype, frac):
     sel = oracle.select(imp.numpy(), budget)
     got, want = run_compact(k, v, sel, 5, budget)
     check_cache(got, want, dtype)
+
+
+def test_compact_and_merge_random_shapes():
+    """Seeded random shapes for the gather and for both merging variants."""
+    r = np.random.default_rng(80)
+    for case in range(16):
+        B, L = int(r.integers(1, 3)), int(r.integers(1, 5))
+        Hkv = int(r.choice([1, 2, 5]))
+        D = int(r.choice([64, 128]))
+        dtype = torch.float32 if case % 4 == 3 else torch.bfloat16
+        N = int(r.choice([3, 50, 64, 65, 200, 700, 1500]))
+        frac = float(r.choice([0.05, 0.3, 0.7, 1.0]))
+        g = torch.Generator().manual_seed(5000 + case)
+        k = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+        v = torch.randn((B, L, Hkv, N, D), generator=g).to(dtype)
+        imp = synthetic_importance(B, L, N, seed=5000 + case)
+        budget = max(L + 1, int(frac * L * N))
+        sel = oracle.select(imp.numpy(), budget)
+        cap = int(r.integers(0, 7))
+        got, want = run_compact(k, v, sel, cap, budget)
+        check_cache(got, want, dtype)
+        bf = dtype == torch.bfloat16
+        rtol = 2.0 ** -7 if bf else 2e-6
+
+        def compare():
+            torch.cuda.synchronize()
+            kc, vc = np32(got.kc), np32(got.vc)
+            for b in range(B):
+                for l in range(L):
+                    off, cp, n = int(want["seg_off"][b, l]), int(want["caps"][b, l]), int(want["lens"][b, l])
+                    gk = kc[off * Hkv * D:(off + cp) * Hkv * D].reshape(Hkv, cp, D)[:, :n]
+                    gv = vc[off * Hkv * D:(off + cp) * Hkv * D].reshape(Hkv, cp, D)[:, :n]
+                    np.testing.assert_allclose(gk, oracle.segment(want, "kc", b, l)[:, :n], rtol=rtol, atol=1e-4)
+                    np.testing.assert_allclose(gv, oracle.segment(want, "vc", b, l)[:, :n], rtol=rtol, atol=1e-4)
+
+        if case % 2 == 0 or not bf:
+            P.prefixkv_merge_position(got, k.to(DEV), v.to(DEV))
+            oracle.merge_position(want, np32(k), np32(v), storage_bf16=bf)
+            compare()
+        else:
+            match = P.prefixkv_merge_feature(got, k.to(DEV), v.to(DEV)).cpu().numpy()
+            for plane, nm, src in ((0, "kc", np32(k)), (1, "vc", np32(v))):
+                wm, best = oracle.feature_match(want, src)
+                np.testing.assert_array_equal(match[plane] == -1, wm == -1)
+                assert (oracle.match_cosine(want, src, match[plane]) >= best - 5e-6).all()
+                oracle.merge_by_match(want, nm, src, match[plane], storage_bf16=True)
+            compare()
 
 
 def test_compact_with_empty_segments():
