@@ -103,6 +103,7 @@ compact_gather_kernel(int nchunk, int Hkv, int L, int row_bytes, const unsigned 
 #pragma unroll
         for (int i = 0; i < kRows / RPI; ++i) {
             const int r = r0 + i * RPI + rsel;
+            kr[i] = vr[i] = make_uint4(0, 0, 0, 0);   // (defined on every path: the arrays stay in registers)
             if (r < len) {
                 const int pos = kept_pos[off + r];
                 kr[i] = *(const uint4*)(kb + ks.n * pos * (int64_t)esize + sub * 16);
