@@ -833,7 +833,12 @@ static hipError_t launch_decode_s(const DecodeParams& p, int shape, int nblk, hi
         // more workgroups than fit on the chip at once: smaller register footprint, twice as many resident
         // workgroups with a quarter of the loads in flight each (measured 4-27 % faster from batch 2 on)
         constexpr int NI4 = NI_MAX < 4 ? NI_MAX : 4;
-        if (shape == 0 && nblk > 4 * compute_units()) {
+        const bool one_round = nblk <= 4 * compute_units();
+        // bf16 rows: the two-wavefront shapes also serve longer prompts (measured at N = 1500 .. 8192: 4-18 %
+        // faster than four or eight wavefronts per workgroup, whose register budget spills) except when
+        // segments of more than 4096 rows meet a launch of several rounds
+        if (BF16 && (shape == 1 || (shape == 2 && one_round))) shape = 0;
+        if (shape == 0 && !one_round) {
             hipLaunchKernelGGL((decode_attn_kernel<BF16, LPR, G, NI4, 2, 4, EV>), dim3(nblk), dim3(2 * kWave), 0, st, p);
             return hipGetLastError();
         }

@@ -549,9 +549,9 @@ def run_decode_case(B, L, H, Hkv, N, D, dtype, frac, steps, seed, layer_range=No
     (1, 2, 6, 2, 150, 128, torch.bfloat16, 0.4, 2),     # group of 3: falls back to 1 head per unit
     (1, 2, 4, 2, 90, 128, torch.float32, 0.9, 2),       # fp32 rows of 512 B (two sub-blocks per chunk)
     (1, 2, 2, 2, 63, 128, torch.bfloat16, 1.0, 2),      # 63 -> 64 -> 65 slots: crosses a chunk edge
-    (1, 2, 4, 4, 1500, 128, torch.bfloat16, 0.7, 2),    # N > 1024: 4-wavefront launch shape
-    (1, 2, 8, 2, 4200, 128, torch.bfloat16, 0.8, 2),    # N > 4096: 8-wavefront launch shape, GQA
-    (1, 1, 2, 2, 5000, 64, torch.float32, 0.9, 1),      # long fp32 segment
+    (1, 2, 4, 4, 1500, 128, torch.bfloat16, 0.7, 2),    # N > 1024: long segments on the two-wavefront shape
+    (1, 2, 8, 2, 4200, 128, torch.bfloat16, 0.8, 2),    # N > 4096, GQA: split segments
+    (1, 1, 2, 2, 5000, 64, torch.float32, 0.9, 1),      # long fp32 segment: 8-wavefront launch shape
     (1, 2, 4, 2, 3000, 128, torch.bfloat16, 0.9, 2),    # grouped (2 heads per KV head), segments split in 3 pieces
     (1, 2, 16, 2, 2500, 64, torch.bfloat16, 0.95, 2),   # grouped (8 heads), D = 64, split segments
     (2, 3, 8, 2, 1100, 128, torch.bfloat16, 0.95, 3),   # the appended row crosses a piece boundary (1024)
