@@ -125,9 +125,9 @@ compact_gather_kernel(int nchunk, int Hkv, int L, int row_bytes, const unsigned 
 // position is averaged into the nearest kept one (half way: the lower), keys and values of all heads
 // alike.  The kept positions ascend along the slots, so the positions matched to slot j are the contiguous
 // range (mid(j-1), mid(j)] with mid(j) = floor((kept_pos[j] + kept_pos[j+1]) / 2): no matching pass is
-// needed.  One workgroup per (segment, kv head, part of the slot list); a wavefront takes every 4th slot of
-// the part and walks its range with 64/LPR rows per load instruction, two instructions deep; the row
-// groups' fp32 sums are added in a fixed order.  Every row of K and V is read exactly once per launch.
+// needed.  One workgroup per (segment, kv head, part of the slot list); a row group of a wavefront takes a slot
+// and sums its range in ascending order (long ranges: the whole wavefront, 64/LPR rows per load instruction, the
+// groups' sums added in a fixed order).  Every row of K and V is read exactly once per launch.
 template <int LPR, bool BF16>
 __global__ void __launch_bounds__(256)
 merge_position_kernel(int nparts, int Hkv, int L, int N, int row_bytes, const unsigned char* __restrict__ k,
@@ -151,59 +151,90 @@ merge_position_kernel(int nparts, int Hkv, int L, int N, int row_bytes, const un
     const unsigned char* kb = k + (ks.b * b + ks.l * l + ks.h * h) * (int64_t)esize + sub * 16;
     const unsigned char* vb = v + (vs.b * b + vs.l * l + vs.h * h) * (int64_t)esize + sub * 16;
     const int64_t kstep = ks.n * (int64_t)esize, vstep = vs.n * (int64_t)esize;
-    for (int j = j0 + wv; j < j1; j += 4) {
-        const int pj = kp[j];
-        const int lo = j == 0 ? 0 : (kp[j - 1] + pj) / 2 + 1;
-        const int hi = j == len - 1 ? N : (pj + kp[j + 1]) / 2 + 1;
-        float ka[EPL], va[EPL];
+    // accumulate one row chunk (16 bytes of this lane) into fp32 sums
+    auto add16 = [](float (&acc)[EPL], const uint4& r) {
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
-        for (int x = 0; x < EPL; ++x) { ka[x] = 0.f; va[x] = 0.f; }
-        for (int m0 = lo; m0 < hi; m0 += 2 * RPI) {
-            const int ma = m0 + rg, mb = m0 + RPI + rg;
-            uint4 r[4];
-            r[0] = r[1] = r[2] = r[3] = make_uint4(0, 0, 0, 0);   // zero bits are 0.0 in both formats
-            if (ma < hi) { r[0] = *(const uint4*)(kb + kstep * ma); r[1] = *(const uint4*)(vb + vstep * ma); }
-            if (mb < hi) { r[2] = *(const uint4*)(kb + kstep * mb); r[3] = *(const uint4*)(vb + vstep * mb); }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const uint32_t w[4] = {r[t].x, r[t].y, r[t].z, r[t].w};
-                float* acc = (t & 1) ? va : ka;
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    if constexpr (BF16) {
-                        acc[2 * x] += __uint_as_float(w[x] << 16);
-                        acc[2 * x + 1] += __uint_as_float(w[x] & 0xffff0000u);
-                    } else {
-                        acc[x] += __uint_as_float(w[x]);
-                    }
-                }
+        for (int x = 0; x < 4; ++x) {
+            if constexpr (BF16) {
+                acc[2 * x] += __uint_as_float(w[x] << 16);
+                acc[2 * x + 1] += __uint_as_float(w[x] & 0xffff0000u);
+            } else {
+                acc[x] += __uint_as_float(w[x]);
             }
         }
+    };
+    auto store_mean = [&](int j, const float (&ka)[EPL], const float (&va)[EPL], float cnt) {
+        const int64_t dst = (off * Hkv + (int64_t)h * cap + j) * row_bytes + sub * 16;
+        if constexpr (BF16) {
+            uint32_t ko[4], vo[4];
 #pragma unroll
-        for (int sh = LPR; sh < kWave; sh <<= 1)
-#pragma unroll
-            for (int x = 0; x < EPL; ++x) {
-                ka[x] += __shfl_xor(ka[x], sh, kWave);
-                va[x] += __shfl_xor(va[x], sh, kWave);
+            for (int x = 0; x < 4; ++x) {
+                ko[x] = (uint32_t)f32_to_bf16(ka[2 * x] / cnt) | ((uint32_t)f32_to_bf16(ka[2 * x + 1] / cnt) << 16);
+                vo[x] = (uint32_t)f32_to_bf16(va[2 * x] / cnt) | ((uint32_t)f32_to_bf16(va[2 * x + 1] / cnt) << 16);
             }
-        if (rg == 0) {
-            const float cnt = (float)(hi - lo);      // >= 1: the range holds the kept position itself
-            const int64_t dst = (off * Hkv + (int64_t)h * cap + j) * row_bytes + sub * 16;
-            if constexpr (BF16) {
-                uint32_t ko[4], vo[4];
+            *(uint4*)(kc + dst) = make_uint4(ko[0], ko[1], ko[2], ko[3]);
+            *(uint4*)(vc + dst) = make_uint4(vo[0], vo[1], vo[2], vo[3]);
+        } else {
+            *(uint4*)(kc + dst) = make_uint4(__float_as_uint(ka[0] / cnt), __float_as_uint(ka[1] / cnt),
+                                             __float_as_uint(ka[2] / cnt), __float_as_uint(ka[3] / cnt));
+            *(uint4*)(vc + dst) = make_uint4(__float_as_uint(va[0] / cnt), __float_as_uint(va[1] / cnt),
+                                             __float_as_uint(va[2] / cnt), __float_as_uint(va[3] / cnt));
+        }
+    };
+    // A wavefront takes RPI consecutive slots at a time, one per row group (LPR lanes = one row): a group walks
+    // the range of its slot two rows deep and holds the whole sums, no exchange between lanes.  A range longer
+    // than kLongRange rows (a layer that keeps little of a long prompt) is walked by the whole wavefront
+    // afterwards, RPI rows per load instruction, and the groups' sums are added in a fixed order.
+    constexpr int kLongRange = 32;
+    for (int jb = j0 + wv * RPI; jb < j1; jb += 4 * RPI) {
+        const int j = jb + rg;
+        const bool act = j < j1;
+        int lo = 0, hi = 0;
+        if (act) {
+            const int pj = kp[j];
+            lo = j == 0 ? 0 : (kp[j - 1] + pj) / 2 + 1;
+            hi = j == len - 1 ? N : (pj + kp[j + 1]) / 2 + 1;
+        }
+        const bool is_long = act && hi - lo > kLongRange;
+        const unsigned long long longmask = __builtin_amdgcn_ballot_w64(is_long && sub == 0);
+        if (act && !is_long) {
+            float ka[EPL], va[EPL];
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    ko[x] = (uint32_t)f32_to_bf16(ka[2 * x] / cnt) | ((uint32_t)f32_to_bf16(ka[2 * x + 1] / cnt) << 16);
-                    vo[x] = (uint32_t)f32_to_bf16(va[2 * x] / cnt) | ((uint32_t)f32_to_bf16(va[2 * x + 1] / cnt) << 16);
+            for (int x = 0; x < EPL; ++x) { ka[x] = 0.f; va[x] = 0.f; }
+            for (int m = lo; m < hi; m += 2) {
+                uint4 r[4];
+                r[2] = r[3] = make_uint4(0, 0, 0, 0);     // zero bits are 0.0 in both formats
+                r[0] = *(const uint4*)(kb + kstep * m);
+                r[1] = *(const uint4*)(vb + vstep * m);
+                if (m + 1 < hi) { r[2] = *(const uint4*)(kb + kstep * (m + 1)); r[3] = *(const uint4*)(vb + vstep * (m + 1)); }
+                add16(ka, r[0]); add16(va, r[1]); add16(ka, r[2]); add16(va, r[3]);
+            }
+            store_mean(j, ka, va, (float)(hi - lo));      // >= 1 row: the range holds the kept position itself
+        }
+        for (unsigned long long lm = longmask; lm; lm &= lm - 1) {
+            const int src = __builtin_ctzll(lm);          // first lane of the group that owns the long slot
+            const int jl = jb + src / LPR;
+            const int llo = __shfl(lo, src, kWave), lhi = __shfl(hi, src, kWave);
+            float ka[EPL], va[EPL];
+#pragma unroll
+            for (int x = 0; x < EPL; ++x) { ka[x] = 0.f; va[x] = 0.f; }
+            for (int m0 = llo; m0 < lhi; m0 += 2 * RPI) {
+                const int ma = m0 + rg, mb = m0 + RPI + rg;
+                uint4 r[4];
+                r[0] = r[1] = r[2] = r[3] = make_uint4(0, 0, 0, 0);
+                if (ma < lhi) { r[0] = *(const uint4*)(kb + kstep * ma); r[1] = *(const uint4*)(vb + vstep * ma); }
+                if (mb < lhi) { r[2] = *(const uint4*)(kb + kstep * mb); r[3] = *(const uint4*)(vb + vstep * mb); }
+                add16(ka, r[0]); add16(va, r[1]); add16(ka, r[2]); add16(va, r[3]);
+            }
+#pragma unroll
+            for (int sh = LPR; sh < kWave; sh <<= 1)
+#pragma unroll
+                for (int x = 0; x < EPL; ++x) {
+                    ka[x] += __shfl_xor(ka[x], sh, kWave);
+                    va[x] += __shfl_xor(va[x], sh, kWave);
                 }
-                *(uint4*)(kc + dst) = make_uint4(ko[0], ko[1], ko[2], ko[3]);
-                *(uint4*)(vc + dst) = make_uint4(vo[0], vo[1], vo[2], vo[3]);
-            } else {
-                *(uint4*)(kc + dst) = make_uint4(__float_as_uint(ka[0] / cnt), __float_as_uint(ka[1] / cnt),
-                                                 __float_as_uint(ka[2] / cnt), __float_as_uint(ka[3] / cnt));
-                *(uint4*)(vc + dst) = make_uint4(__float_as_uint(va[0] / cnt), __float_as_uint(va[1] / cnt),
-                                                 __float_as_uint(va[2] / cnt), __float_as_uint(va[3] / cnt));
-            }
+            if (rg == 0) store_mean(jl, ka, va, (float)(lhi - llo));
         }
     }
 }
@@ -218,8 +249,10 @@ hipError_t launch_merge_position(const pkv_shape& s, const void* k, Strides ks, 
     const int esize = bf16 ? 2 : 4;
     const int row_bytes = s.D * esize;
     const int lpr = row_bytes / 16;
-    // enough workgroups to fill the chip a few times over, but never tiny ones
-    int nparts = (4096 + nseg * s.Hkv - 1) / (nseg * s.Hkv);
+    // enough workgroups to fill the chip, but few: a workgroup's start (segment state, kept positions) is a chain
+    // of dependent loads, and more, smaller workgroups were slower at every size measured
+    const int want = s.N <= 1024 ? 2048 : 1024;
+    int nparts = (want + nseg * s.Hkv - 1) / (nseg * s.Hkv);
     nparts = nparts < 1 ? 1 : (nparts > 8 ? 8 : nparts);
     dim3 grid((uint32_t)((size_t)nparts * s.Hkv * nseg));
 #define PKV_MERGE(LPR, BF)                                                                                   \
