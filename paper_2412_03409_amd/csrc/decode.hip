@@ -828,7 +828,7 @@ static hipError_t launch_decode_s(const DecodeParams& p, int shape, int nblk, hi
     constexpr bool WIDE = G >= 4;
     constexpr int NI16 = WIDE ? (NI_MAX < 8 ? NI_MAX : 8) : (NI_MAX < 16 ? NI_MAX : 16);
     constexpr int NI8 = NI_MAX < 8 ? NI_MAX : 8;
-    constexpr int OCC4 = WIDE ? 2 : 4;
+    constexpr int OCC4 = WIDE ? 2 : 3;   // the 4- and 8-wavefront shapes spill at 4 wavefronts/SIMD (8-9 % slower)
     if constexpr (!WIDE) {
         // more workgroups than fit on the chip at once: smaller register footprint, twice as many resident
         // workgroups with a quarter of the loads in flight each (measured 4-27 % faster from batch 2 on)
