@@ -902,9 +902,9 @@ static hipError_t launch_gqa_s(DecodeParams p, const pkv_shape& s, int* ws, hipS
     int grid = compute_units() * (8 / W);
     const long long most = (long long)lay.pieces_cap * (s.H / G);
     if (grid > most) grid = (int)most;
-    // 64-row blocks; 32-row blocks for eight heads of dimension 128, whose 64 output accumulators per lane
-    // leave no room for the 32 loads of a 64-row block (the larger block spills; measured 54.1 vs 50.7 us per step)
-    constexpr int NT = (G == 8 && D == 128) ? 2 : 4;
+    // 32-row blocks: with 64-row blocks the eight-head kernel spills at D = 128 (54.1 vs 50.7 us per step) and
+    // the four-head kernel sits at the register limit (124.2 vs 119.9 us per step on the long-context workload)
+    constexpr int NT = 2;
     hipLaunchKernelGGL((decode_gqa_kernel<D, G, NT, W, 2, EV>), dim3(grid), dim3(W * kWave), 0, st, p);
     return hipGetLastError();
 }
