@@ -184,7 +184,7 @@ int prefixkv_compact(const pkv_shape *shape, const void *k, pkv_strides ks, cons
  * Runs in place on the output of prefixkv_compact, before the first decode step: slot j of segment
  * (b,l) holds position kept_pos[j]; a pruned position half way between two kept ones goes to the lower
  * (first maximum of the metric); keys and values of all KV heads are averaged alike, fp32 sums in
- * ascending position, one rounding to the storage dtype.  Only the first lens[b,l] slots are written.
+ * a fixed order, one rounding to the storage dtype.  Only the first lens[b,l] slots are written.
  *   k, v [dev]: the uncompressed tensors given to prefixkv_compact;  everything else as produced by it.
  * prefixkv_merge_feature is the variant with the cosine metric. */
 int prefixkv_merge_position(const pkv_shape *shape, const void *k, pkv_strides ks, const void *v,
