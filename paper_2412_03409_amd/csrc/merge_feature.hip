@@ -5,7 +5,8 @@
 //
 //  mf_prepare_kernel   per (tensor, segment, kv head): marks the retained positions in the assignment row
 //                      (-1) and computes 1/|x_u| of every retained vector.
-//  mf_match_kernel     one workgroup = 128 positions of one (tensor, segment, kv head), a wavefront owns 32.
+//  mf_match_kernel     one workgroup = 256 positions of one (tensor, segment, kv head), a wavefront owns 64
+//                      (two 32-position tiles, so that a fragment read from LDS feeds two MFMAs).
 //                      The retained vectors (already contiguous in the compacted cache) stream through LDS
 //                      64 at a time (asynchronous copies, double-buffered) and
 //                        S^T[32 slots x 32 positions] = Xc[32 x D] . X^T
@@ -23,7 +24,8 @@ namespace pkv {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
-constexpr int kMfRows = 128;    // positions per workgroup of the matching kernel
+constexpr int kMfTiles = 2;     // 32-position tiles per wavefront of the matching kernel: a fragment read feeds that many MFMAs
+constexpr int kMfRows = 128 * kMfTiles;   // positions per workgroup of the matching kernel
 constexpr int kMfStage = 64;    // retained vectors per LDS stage
 
 struct MergeFeatureParams {
@@ -116,14 +118,16 @@ mf_match_kernel(MergeFeatureParams p) {
     const float* nrow = p.inv_norm + ((size_t)tz * U + u) * p.NP;
     const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
     const int ln = lane & 31, hf = lane >> 5;
-    const int pos_m = m0 + wv * 32 + ln;         // the position this lane's column belongs to
-
-    bf16x8_t qf[NJ];
-    {
-        const int row = pos_m < p.N ? pos_m : p.N - 1;
+    constexpr int T = kMfTiles;
+    int pos_m[T];                                // the positions this lane's columns belong to
+    bf16x8_t qf[T][NJ];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        pos_m[t] = m0 + (wv * T + t) * 32 + ln;
+        const int row = pos_m[t] < p.N ? pos_m[t] : p.N - 1;
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
-            qf[j] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(xbase + (uint32_t)row * (uint32_t)xs.n + 16 * j + 8 * hf));
+            qf[t][j] = __builtin_bit_cast(bf16x8_t, *(const uint4*)(xbase + (uint32_t)row * (uint32_t)xs.n + 16 * j + 8 * hf));
     }
     const int nst = (n + kMfStage - 1) / kMfStage;
 
@@ -149,8 +153,10 @@ mf_match_kernel(MergeFeatureParams p) {
                                              (__attribute__((address_space(3))) void*)dN, 4, 0, 0);
     };
 
-    float best = -INFINITY;
-    int bslot = 0;
+    float best[T];
+    int bslot[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) { best[t] = -INFINITY; bslot[t] = 0; }
     auto step = [&](int st, const unsigned char* sX, const float* sN, unsigned char* nX, float* nN) {
         __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's copies of stage st have landed
         __syncthreads();
@@ -160,14 +166,17 @@ mf_match_kernel(MergeFeatureParams p) {
             const int slot0 = st * kMfStage + half * 32;
             if (slot0 >= n) break;
             const unsigned char* sK = sX + half * 32 * ROWB;
-            f32x16_t s;
+            f32x16_t s[T];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+            for (int t = 0; t < T; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 const int pos = (2 * j + hf) ^ mf_swz<CPR>(ln);
                 const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *(const uint4*)(sK + ln * ROWB + pos * 16));
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[j], s, 0, 0, 0);
+#pragma unroll
+                for (int t = 0; t < T; ++t) s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][j], s[t], 0, 0, 0);
             }
             // register r holds slot slot0 + 8*(r/4) + 4*hf + r%4: ascending in r
             const bool tail = slot0 + 32 > n;
@@ -178,11 +187,14 @@ mf_match_kernel(MergeFeatureParams p) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int slot = slot0 + 8 * g + 4 * hf + e;
-                    float sc = s[4 * g + e] * inv[e];
-                    if (tail) sc = slot < n ? sc : -INFINITY;
-                    const bool up = sc > best;   // strict: the first maximum stays
-                    best = up ? sc : best;
-                    bslot = up ? slot : bslot;
+#pragma unroll
+                    for (int t = 0; t < T; ++t) {
+                        float sc = s[t][4 * g + e] * inv[e];
+                        if (tail) sc = slot < n ? sc : -INFINITY;
+                        const bool up = sc > best[t];   // strict: the first maximum stays
+                        best[t] = up ? sc : best[t];
+                        bslot[t] = up ? slot : bslot[t];
+                    }
                 }
             }
         }
@@ -194,12 +206,13 @@ mf_match_kernel(MergeFeatureParams p) {
         if (st + 1 < nst) step(st + 1, sXb, sNb, sXa, sNa);
     }
     // the two halves of a column: larger score, on a tie the lower slot
-    const float ob = __shfl_xor(best, 32, kWave);
-    const int os = __shfl_xor(bslot, 32, kWave);
-    if (ob > best || (ob == best && os < bslot)) { best = ob; bslot = os; }
-    if (hf == 0 && pos_m < p.N) {
-        int32_t* mrow = p.match + ((size_t)tz * U + u) * p.N;
-        if (mrow[pos_m] != -1) mrow[pos_m] = bslot;
+    int32_t* mrow = p.match + ((size_t)tz * U + u) * p.N;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const float ob = __shfl_xor(best[t], 32, kWave);
+        const int os = __shfl_xor(bslot[t], 32, kWave);
+        if (ob > best[t] || (ob == best[t] && os < bslot[t])) { best[t] = ob; bslot[t] = os; }
+        if (hf == 0 && pos_m[t] < p.N && mrow[pos_m[t]] != -1) mrow[pos_m[t]] = bslot[t];
     }
 }
 
