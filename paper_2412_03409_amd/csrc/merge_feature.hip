@@ -273,7 +273,17 @@ mf_average_kernel(MergeFeatureParams p) {
                 const uint32_t a = keys[i], c = keys[q];
                 if ((a > c) == ((i & k) == 0)) { keys[i] = c; keys[q] = a; }
             }
-            __syncthreads();
+            // the 64 pairs a wavefront takes per turn of a stage with partner distance j <= 64 lie in one aligned
+            // block of 128 keys, the same for all such stages: only a stage that reaches further (or is followed
+            // by one that does) has to meet the other wavefronts
+            const int jn = j > 1 ? (j >> 1) : k;
+            if (j > kWave || jn > kWave) {
+                __syncthreads();
+            } else {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
         }
 
     // slots per wavefront and turn: up to 64, fewer when that leaves wavefronts without work
