@@ -169,6 +169,8 @@ int prefixkv_offline_config(int S, int L, int N, const int32_t *sample_lengths,
  * offsets (one int per slot).  lens[b,l] = lengths[b,l] = the number of occupied slots.
  * kc, vc must hold at least prefixkv_cache_tokens_upper_bound() tokens * Hkv * D elements and
  * kept_pos that many ints.  Slots beyond lens are not written.
+ * N + decode_capacity must stay below 2^20 slots (PKV_ERR_DIM otherwise): the decode entry points
+ * keep a completion count above bit 20 of lens and address a segment's rows with 32-bit offsets.
  *   k, v [dev] [B,L,Hkv,N,D] with strides; order [dev] [B,L,N]; lengths [dev] [B,L]
  *   seg_off [dev] i64 [B,L], caps [dev] i32 [B,L], lens [dev] i32 [B,L]: out */
 int prefixkv_compact(const pkv_shape *shape, const void *k, pkv_strides ks, const void *v,
@@ -233,7 +235,8 @@ int64_t prefixkv_cache_tokens_upper_bound(int B, int64_t budget_tokens, int L, i
  *   out[b,l,h,:] = sum_j softmax_j(scale[l] * q[b,l,h,:].kc_j) * vc_j   over the lens slots of kv
  * head g(h); an empty segment gives zeros.  fp32 softmax and accumulation; out in shape->dtype.
  *   q, out [dev] [B,L,H,D] dense;  k_new, v_new [dev] [B,L,Hkv,D] dense or NULL (both)
- *   kc, vc, seg_off, caps as produced by prefixkv_compact
+ *   kc, vc, seg_off, caps as produced by prefixkv_compact (every caps entry below 2^20, which
+ *       prefixkv_compact enforces through N + decode_capacity < 2^20)
  *   lens [dev] in/out: plain lengths below 2^20 before and after the call.  WHILE the launch runs
  *       the library keeps a completion count in the bits above 2^20 of each entry, so lens must
  *       not be read or written by anything else until the launch has finished.  H <= 2048.
@@ -271,7 +274,7 @@ int prefixkv_decode_attn(const pkv_shape *shape, int l0, int l1, const void *q, 
  *   kept_pos  [dev] i32 or NULL: if given, slot labels are maintained: N+j-1 for decode token j in the
  *       ring and in the permanent region, -1 for a ring slot whose token was decided
  *   t: 1-based decode step since prefixkv_compact;  1 <= distance <= 65535
- * Everything else as in prefixkv_decode_attn (k_new, v_new required). */
+ * Everything else as in prefixkv_decode_attn (k_new, v_new required; caps below 2^20). */
 int prefixkv_decode_attn_evict(const pkv_shape *shape, int l0, int l1, const void *q,
                                const void *k_new, const void *v_new, const float *scale, void *kc,
                                void *vc, const int64_t *seg_off, const int32_t *caps,

@@ -23,14 +23,29 @@ _LIB = _HERE / "libprefixkv_oracle.so"
 NONFINITE, NEGATIVE, ZERO_LAYER, RANGE = 1, 2, 4, 8
 
 
-def build(force: bool = False) -> Path:
-    """Compile the oracle with gcc (fp64 arithmetic must stay in source order: no -ffast-math)."""
-    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
-        tmp = _LIB.with_suffix(".so.tmp%d" % os.getpid())
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp",
+_LIB_SAN = _HERE / "libprefixkv_oracle_san.so"
+# PKV_ORACLE_SANITIZE=1 makes lib() load the build with AddressSanitizer and UndefinedBehaviorSanitizer
+# (the process must then run with the gcc sanitizer runtime preloaded; tests/test_oracle_sanitized.py does).
+_SANITIZE = os.environ.get("PKV_ORACLE_SANITIZE", "0") == "1"
+
+
+def build(force: bool = False, sanitize: bool = False) -> Path:
+    """Compile the oracle with gcc (fp64 arithmetic must stay in source order: no -ffast-math).
+    sanitize=True builds the checked variant (-fsanitize=address,undefined -O1) beside it."""
+    out = _LIB_SAN if sanitize else _LIB
+    if force or not out.exists() or out.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = out.with_suffix(".so.tmp%d" % os.getpid())
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+               "-fno-omit-frame-pointer"] if sanitize else ["-O2"]
+        subprocess.check_call(["gcc", *opt, "-std=c99", "-fPIC", "-shared", "-fopenmp",
                                "-ffp-contract=off", "-o", str(tmp), str(_SRC), "-lm"])
-        os.replace(tmp, _LIB)
-    return _LIB
+        os.replace(tmp, out)
+    return out
+
+
+def sanitizer_runtime() -> str:
+    """Path of gcc's AddressSanitizer runtime, to be preloaded by a process that loads the checked build."""
+    return subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
 
 
 _lib = None
@@ -39,7 +54,7 @@ _lib = None
 def lib() -> C.CDLL:
     global _lib
     if _lib is None:
-        _lib = C.CDLL(str(build()))
+        _lib = C.CDLL(str(build(sanitize=_SANITIZE)))
         _lib.pkvo_threads.restype = C.c_int
         _lib.pkvo_decode_attn.restype = C.c_int
         _lib.pkvo_sort_prefix_layer.restype = C.c_int

@@ -169,8 +169,9 @@ static int pkvo_rem_asc(const void *a, const void *b) {
     return (x->l > y->l) - (x->l < y->l);
 }
 
-/* Proportional rescale of per-layer weights to an exact token budget (the "scale the resulting global
- * prefix configuration to meet the target budget" step of Sec. 3.3): lengths[l] = weight[l]*budget/K
+/* Proportional rescale of per-layer weights to an exact token budget (Sec. 3.3, last paragraph: once
+ * the search has stopped within its threshold, the configuration it found is brought to the target
+ * budget by scaling): lengths[l] = weight[l]*budget/K
  * rounded down and clamped to [1,N] (K = sum of the weights), then the missing tokens go one per
  * layer in order of largest remainder (ties: lower layer), cyclically; a surplus is taken back in order
  * of smallest remainder.  Requires L < budget < L*N and K > 0. */
@@ -202,7 +203,7 @@ static void pkvo_rescale(int L, int N, const int64_t *weight, int64_t K, int64_t
 
 /* ---------------------------------------------------------------------------------------------
  * Stage 3 -- Algorithm 1 (binary search for the retention ratio p) for ONE sequence, followed by
- * the "scale the configuration to meet the budget" step of Sec. 3.3's last paragraph.
+ * the rescale to the exact budget of Sec. 3.3's last paragraph.
  * cum [L,N]; budget/tol in tokens.  Outputs lengths[L], *p, *iters, *raw_total (sum of lengths of
  * the last evaluated p, before scaling).
  * ------------------------------------------------------------------------------------------- */

@@ -135,6 +135,9 @@ int prefixkv_compact(const pkv_shape* s, const void* k, pkv_strides ks, const vo
     if (!s || !k || !v || !order || !lengths || !seg_off || !caps || !kc || !vc || !kept_pos || !lens)
         return PKV_ERR_NULL;
     if (!shape_ok(s) || decode_capacity < 0) return PKV_ERR_DIM;
+    // the decode kernels keep a completion count in bits 20 and up of lens and address the rows of a
+    // segment with 32-bit byte offsets: a segment (N + decode_capacity slots at most) stays below 2^20
+    if ((int64_t)s->N + decode_capacity >= kMaxSegmentSlots) return PKV_ERR_DIM;
     if (!dtype_ok(s)) return PKV_ERR_DTYPE;
     const int esize = s->dtype == PKV_F32 ? 4 : 2;
     if (!strides_ok(ks, esize) || !strides_ok(vs, esize) || !aligned16(k) || !aligned16(v) ||

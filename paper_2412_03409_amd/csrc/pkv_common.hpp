@@ -12,6 +12,7 @@ namespace pkv {
 constexpr int kWave = 64;
 constexpr int kMaxL = 64;
 constexpr int kMaxN = 8192;
+constexpr int64_t kMaxSegmentSlots = 1 << 20;   // slots of one (b,l) segment: prompt entries + decode capacity
 constexpr int kDecodeChunk = 64;   // tokens of one (b,l,kv-head) segment handled by one wave
 constexpr int kXcds = 8;           // L2 slices (XCDs) of the chip; workgroup id % 8 picks the XCD
 

@@ -169,6 +169,8 @@ def test_compact_and_decode_argument_errors():
         C.byref(sh), k, ks, FAKE, st, FAKE, FAKE, cap, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0, None)
     assert comp(k=None) == 1
     assert comp(cap=-1) == 2
+    assert comp(cap=(1 << 20) - 128) == 2     # N + decode_capacity reaches 2^20 slots per segment
+    assert comp(cap=(1 << 20) - 129, ks=Bd._Strides(0, 0, 0, 6)) == 4   # one below the bound passes the size check
     assert comp(sh=_shape(D=32)) == 2
     assert comp(ks=Bd._Strides(0, 0, 0, 6)) == 4
     dec = lambda l0=0, l1=4, q=FAKE, kn=FAKE, vn=FAKE, sh=s: lib.prefixkv_decode_attn(

@@ -136,6 +136,27 @@ def test_gqa_long_sampled_sequence_and_tail_columns():
     run_config("gqa_long", 0.1, sample_b=2, steps=2, imp_layers=[0, 19], imp_tail=160)
 
 
+@pytest.mark.timeout(600)
+def test_gqa_long_every_column_of_the_sharpest_layer():
+    """All 8192 columns of one (sequence, layer) at the long-context size against the oracle: the early
+    columns accumulate over thousands of query rows and hold the sink keys.  The layer with the
+    largest logit scale is taken (its sink columns dominate), and one with the smallest."""
+    w = CONFIGS["gqa_long"]
+    x = make_prefill(w, device=DEV)
+    imp = P.prefixkv_importance(x["q"], x["k"], x["scale"])
+    torch.cuda.synchronize()
+    scale = x["scale"].cpu().numpy()
+    b = 1
+    for l in (int(np.argmax(scale)), int(np.argmin(scale))):
+        print(f"gqa_long importance, all columns: sequence {b}, layer {l}, scale {scale[l]:.4f}", flush=True)
+        want = oracle.importance(f32(x["q"][b:b + 1, l:l + 1]), f32(x["k"][b:b + 1, l:l + 1]), scale[l:l + 1])
+        got = imp[b:b + 1, l:l + 1].cpu().numpy()
+        assert got.shape == want.shape == (1, 1, w.N)
+        check_importance(got, want)
+        top = np.argsort(-want[0, 0])[:8]
+        print("  largest columns", top.tolist(), "importance", np.round(want[0, 0, top], 2).tolist(), flush=True)
+
+
 def run_config_pruning(name, budget, sample_b, steps, d):
     """The same pipeline with the decode loop pruning at distance d (one HIP graph of `steps` launches);
     the sampled sequence is checked against the oracle step by step, the whole batch against the closed

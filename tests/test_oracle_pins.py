@@ -153,6 +153,30 @@ def test_prefix_exact_integer_cumsum():
     assert np.max(np.abs(prefix - ref)) <= N * 2.0 ** -36 + 2.0 ** -23
 
 
+def test_prefix_weights_round_down_for_tiny_importance():
+    """Importance below 2^-13 has a fractional part after the scaling by 2^36 (an fp32 value v has
+    v*2^36 integral only from 2^-13 upwards), so these weights tell floor from round-to-nearest
+    and from ceil: expected sums are exact Python integers."""
+    vals = [3 * 2.0 ** -38, 2.0 ** -37, 1.0, 5 * 2.0 ** -38, 7 * 2.0 ** -39, 2.0 ** -36 + 2.0 ** -37]
+    imp = np.array(vals, np.float32)
+    assert [float(x) for x in imp] == vals  # all exactly representable
+    st, order, cum, prefix = oracle.sort_prefix_layer(imp)
+    assert st == 0
+    exact = [Fraction(v) * 2 ** 36 for v in vals]              # 3/4, 1/2, 2^36, 5/4, 7/8, 3/2
+    assert [e.denominator for e in exact] == [4, 2, 1, 4, 8, 2]
+    w_floor = {i: e.numerator // e.denominator for i, e in enumerate(exact)}
+    assert [w_floor[i] for i in range(6)] == [0, 0, 2 ** 36, 1, 0, 1]
+    np.testing.assert_array_equal(order, [2, 5, 3, 4, 0, 1])   # 2^36, 3/2, 5/4, 7/8, 3/4, 1/2
+    want, tot = [], 0
+    for i in order:
+        tot += w_floor[int(i)]
+        want.append(tot)
+    assert [int(c) for c in cum] == want == [2 ** 36, 2 ** 36 + 1, 2 ** 36 + 2, 2 ** 36 + 2, 2 ** 36 + 2, 2 ** 36 + 2]
+    # a layer made only of such values: floor gives 0, 0, 1 -> sum 1 (rounding would give 3)
+    st, order, cum, prefix = oracle.sort_prefix_layer(np.array([3 * 2.0 ** -38, 2.0 ** -37, 2.0 ** -36], np.float32))
+    assert st == 0 and [int(c) for c in cum] == [1, 1, 1] and order.tolist() == [2, 0, 1]
+
+
 def test_status_bits():
     assert oracle.sort_prefix_layer(np.array([1, np.nan, 2], np.float32))[0] & oracle.NONFINITE
     assert oracle.sort_prefix_layer(np.array([1, np.inf, 2], np.float32))[0] & oracle.NONFINITE
@@ -440,6 +464,30 @@ def test_decode_special_cases():
     import torch
     np.testing.assert_array_equal(ob, torch.from_numpy(oracle.decode_attn(cache, q, None, None, sc))
                                   .to(torch.bfloat16).float().numpy())
+
+
+def test_bf16_output_rounds_ties_to_even():
+    """A cache of one slot returns its value row exactly (softmax weight 1), so the bf16 rounding of
+    the output is seen in isolation: values half way between two bf16 numbers go to the one with the
+    even mantissa, whichever side that is, for both signs; non-ties go to the nearest."""
+    vals = np.array([1 + 2.0 ** -8,        # tie between 1 and 1+2^-7 -> 1 (even)
+                     1 + 3 * 2.0 ** -8,    # tie between 1+2^-7 and 1+2^-6 -> 1+2^-6 (even)
+                     -(1 + 2.0 ** -8), -(1 + 3 * 2.0 ** -8),
+                     1 + 2.0 ** -8 + 2.0 ** -20,   # just above the tie -> up
+                     1 + 3 * 2.0 ** -8 - 2.0 ** -20,  # just below the tie -> down
+                     2.0 ** -10 * (1 + 5 * 2.0 ** -8),  # tie at another exponent: 1+2^-6 (even) vs 1+3*2^-7
+                     0.0], np.float32)
+    want = np.array([1.0, 1 + 2.0 ** -6, -1.0, -(1 + 2.0 ** -6), 1 + 2.0 ** -7, 1 + 2.0 ** -7,
+                     2.0 ** -10 * (1 + 2.0 ** -6), 0.0], np.float32)
+    D = vals.size
+    k = np.ones((1, 1, 1, 1, D), np.float32)
+    v = vals.reshape(1, 1, 1, 1, D).copy()
+    cache = oracle.compact(k, v, np.zeros((1, 1, 1), np.int32), np.ones((1, 1), np.int32), 0)
+    q = np.full((1, 1, 1, D), 0.25, np.float32)
+    exact = oracle.decode_attn(cache, q, None, None, np.ones(1, np.float32))
+    np.testing.assert_array_equal(exact.reshape(-1), vals)
+    got = oracle.decode_attn(cache, q, None, None, np.ones(1, np.float32), out_bf16=True)
+    np.testing.assert_array_equal(got.reshape(-1), want)
 
 
 def test_empty_cache_segment_gives_zero_output():
