@@ -19,7 +19,8 @@
  *     are in ELEMENTS.  D is 64 or 128, H % Hkv == 0, 1 <= L <= 64, 1 <= N <= 8192, B >= 1.
  *   - Calls that use the same workspace or the same output buffers must be ordered by the
  *     caller (same stream, or events).  The library keeps no state between calls (apart from the
- *     device's compute-unit count, looked up once).
+ *     device's compute-unit count and, for prefixkv_select_static, the address of its built-in
+ *     scratch array, each looked up once per device).
  */
 #ifndef PREFIXKV_H
 #define PREFIXKV_H
@@ -133,6 +134,23 @@ int prefixkv_select(int B, int L, int N, const float *importance /* [dev] [B,L,N
                     float *prefix, int32_t *lengths, double *p_out, int32_t *iters,
                     int64_t *raw_total, int32_t *status, void *ws, size_t ws_bytes,
                     pkv_stream stream);
+
+/* ---- prefixkv_select for callers that cannot allocate device memory at all and therefore have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and bit-identical results as prefixkv_select; the scratch
+ * (one status word per (sequence, layer)) is a fixed array built into the library instead of `ws`:
+ * 65536 words = 256 KB, which every GPU the library runs on holds until the process ends.
+ *   B * L <= prefixkv_static_scratch_segments() (= 65536), else PKV_ERR_WORKSPACE, nothing enqueued.
+ * The call allocates nothing and frees nothing.  The first call on a device looks up the array's
+ * device address (with that device current) and keeps it for the life of the process.
+ * All calls on one GPU share that GPU's array: two calls that may overlap in time on the same GPU
+ * (different streams without an ordering event) race on it; calls on one stream are safe.  The
+ * array's contents after a call are unspecified and nothing in it needs clearing between calls. */
+int prefixkv_select_static(int B, int L, int N, const float *importance /* [dev] [B,L,N] */,
+                           const pkv_select_params *params /* [host] */, int32_t *order,
+                           uint64_t *cum, float *prefix, int32_t *lengths, double *p_out,
+                           int32_t *iters, int64_t *raw_total, int32_t *status, pkv_stream stream);
+int prefixkv_static_scratch_segments(void);
 
 /* ---- Stage 2 alone, for offline estimation (Sec. 3.3, last paragraph: the retention ratios R_l
  * are estimated once from a few random samples and reused).  Same order / cum / prefix as

@@ -71,6 +71,10 @@ def load(path: Optional[str] = None) -> C.CDLL:
     L.prefixkv_select.restype = C.c_int
     L.prefixkv_select.argtypes = [i32, i32, i32, vp, C.POINTER(_SelectParams), vp, vp, vp, vp, vp, vp, vp,
                                   vp, vp, sz, vp]
+    L.prefixkv_select_static.restype = C.c_int
+    L.prefixkv_select_static.argtypes = [i32, i32, i32, vp, C.POINTER(_SelectParams), vp, vp, vp, vp, vp, vp, vp,
+                                         vp, vp]
+    L.prefixkv_static_scratch_segments.restype = C.c_int
     L.prefixkv_rank.restype = C.c_int
     L.prefixkv_rank.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     L.prefixkv_offline_config.restype = C.c_int
@@ -245,6 +249,27 @@ def prefixkv_select(importance: torch.Tensor, budget_tokens: int, tol_tokens: in
     if rc != 0:
         raise PrefixKVError(rc, "prefixkv_select")
     return out
+
+
+def prefixkv_select_static(importance: torch.Tensor, budget_tokens: int, out: SelectResult, tol_tokens: int = 0,
+                           max_iters: int = 64, fixup: bool = True) -> SelectResult:
+    """prefixkv_select without a workspace and without any allocation: `out` must be pre-allocated
+    (all eight tensors; prefix may be None).  B*L <= prefixkv_static_scratch_segments()."""
+    _need_cuda(importance, out.order, out.cum, out.prefix, out.lengths, out.p, out.iters, out.raw_total, out.status)
+    if importance.dtype != torch.float32 or importance.dim() != 3 or not importance.is_contiguous():
+        raise ValueError("importance must be contiguous f32 [B,L,N]")
+    B, L, N = importance.shape
+    prm = _SelectParams(int(budget_tokens), int(tol_tokens), int(max_iters), int(bool(fixup)))
+    rc = load().prefixkv_select_static(B, L, N, _ptr(importance), C.byref(prm), _ptr(out.order), _ptr(out.cum),
+                                       _ptr(out.prefix), _ptr(out.lengths), _ptr(out.p), _ptr(out.iters),
+                                       _ptr(out.raw_total), _ptr(out.status), _stream())
+    if rc != 0:
+        raise PrefixKVError(rc, "prefixkv_select_static")
+    return out
+
+
+def prefixkv_static_scratch_segments() -> int:
+    return int(load().prefixkv_static_scratch_segments())
 
 
 @dataclass

@@ -1,5 +1,6 @@
-// C ABI of libprefixkv: argument validation and dispatch.  No allocation, no synchronisation, no
-// global state; every launch goes to the caller's stream.
+// C ABI of libprefixkv: argument validation and dispatch.  No allocation, no synchronisation; every
+// launch goes to the caller's stream.  The only state kept between calls is looked up once per device:
+// the compute-unit count, and the address of the built-in scratch array of prefixkv_select_static.
 #include "pkv_common.hpp"
 
 using namespace pkv;
@@ -108,6 +109,22 @@ int prefixkv_select(int B, int L, int N, const float* importance, const pkv_sele
                                        iters, raw_total, status, ws, (hipStream_t)stream);
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
 }
+
+int prefixkv_select_static(int B, int L, int N, const float* importance, const pkv_select_params* params,
+                           int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
+                           int32_t* iters, int64_t* raw_total, int32_t* status, pkv_stream stream) {
+    if (!importance || !params || !order || !cum || !lengths || !p_out || !iters || !raw_total || !status)
+        return PKV_ERR_NULL;
+    if (B < 1 || L < 1 || L > kMaxL || N < 1 || N > kMaxN) return PKV_ERR_DIM;
+    if (params->budget_tokens < 1 || params->tol_tokens < 0 || params->max_iters < 1) return PKV_ERR_BUDGET;
+    // the built-in scratch array holds one word per (sequence, layer)
+    if ((int64_t)B * L > select_static_max_segments()) return PKV_ERR_WORKSPACE;
+    const hipError_t e = launch_select_static(B, L, N, importance, *params, order, cum, prefix, lengths, p_out,
+                                              iters, raw_total, status, (hipStream_t)stream);
+    return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;
+}
+
+int prefixkv_static_scratch_segments(void) { return select_static_max_segments(); }
 
 int prefixkv_rank(int B, int L, int N, const float* importance, int32_t* order, uint64_t* cum, float* prefix,
                   int32_t* status, void* ws, size_t ws_bytes, pkv_stream stream) {

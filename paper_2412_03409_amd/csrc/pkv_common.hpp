@@ -51,6 +51,11 @@ hipError_t launch_select(int B, int L, int N, const float* importance, const pkv
                          int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
                          int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, hipStream_t st);
 
+int select_static_max_segments();
+hipError_t launch_select_static(int B, int L, int N, const float* importance, const pkv_select_params& p,
+                                int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
+                                int32_t* iters, int64_t* raw_total, int32_t* status, hipStream_t st);
+
 hipError_t launch_rank(int B, int L, int N, const float* importance, int32_t* order, uint64_t* cum,
                        float* prefix, int32_t* status, void* ws, hipStream_t st);
 hipError_t launch_offline_config(int S, int L, int N, const int32_t* sample_lengths, int64_t budget,

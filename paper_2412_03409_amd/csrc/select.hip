@@ -10,6 +10,8 @@
 // results do not depend on scan order or launch shape.
 #include "pkv_common.hpp"
 
+#include <mutex>
+
 namespace pkv {
 
 __device__ __forceinline__ uint64_t shfl_u64(uint64_t v, int src) {
@@ -453,6 +455,45 @@ hipError_t launch_select(int B, int L, int N, const float* importance, const pkv
                        (int64_t)pr.budget_tokens, (int64_t)pr.tol_tokens, (int)pr.max_iters, (int)pr.fixup,
                        lengths, p_out, iters, raw_total, status);
     return hipGetLastError();
+}
+
+// ---- prefixkv_select for callers that cannot allocate: the per-layer status words live in a
+// file-scope device array instead of a caller workspace.  Every GPU holds its own copy of the array at
+// its own address; that address is looked up once per device (the array's name is only a host-side
+// handle and must never be passed to a kernel).  Nothing in the array has to start at zero:
+// sort_prefix_kernel writes the word of every segment of the call before search_kernel reads it.
+constexpr int kStaticSegments = 65536;                 // B * L of one call at most (256 KB per GPU)
+constexpr int kStaticMaxDevices = 64;
+static __device__ __align__(256) int32_t scratch[kStaticSegments];
+
+namespace {
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kStaticMaxDevices] = {};         // device address of `scratch`, per device ordinal
+}  // namespace
+
+int select_static_max_segments() { return kStaticSegments; }
+
+hipError_t launch_select_static(int B, int L, int N, const float* importance, const pkv_select_params& pr,
+                                int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
+                                int32_t* iters, int64_t* raw_total, int32_t* status, hipStream_t st) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kStaticMaxDevices) return hipErrorInvalidDevice;
+    int32_t* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (g_scratch_ptr[dev] == nullptr) {            // first call on this device, which is current
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (p == nullptr) return hipErrorInvalidSymbol;
+            g_scratch_ptr[dev] = (int32_t*)p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    return launch_select(B, L, N, importance, pr, order, cum, prefix, lengths, p_out, iters, raw_total, status,
+                         ptr, st);
 }
 
 hipError_t launch_rank(int B, int L, int N, const float* importance, int32_t* order, uint64_t* cum,

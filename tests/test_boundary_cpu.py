@@ -90,6 +90,22 @@ def test_select_argument_errors():
     assert call(wsb=3) == 5
 
 
+def test_select_static_argument_errors():
+    lib = P.load()
+    def call(B=1, L=4, N=128, imp=FAKE, budget=10, tol=0, iters=64, lengths=FAKE):
+        prm = Bd._SelectParams(budget, tol, iters, 1)
+        return lib.prefixkv_select_static(B, L, N, imp, C.byref(prm), FAKE, FAKE, None, lengths, FAKE, FAKE, FAKE,
+                                          FAKE, None)
+    assert lib.prefixkv_static_scratch_segments() == 65536
+    assert call(imp=None) == 1
+    assert call(lengths=None) == 1
+    assert call(L=65) == 2
+    assert call(N=8193) == 2
+    assert call(budget=0) == 6
+    assert call(iters=0) == 6
+    assert call(B=65536 // 4 + 1) == 5      # one sequence more than the built-in scratch array holds
+
+
 def test_rank_and_offline_config_argument_errors():
     lib = P.load()
     rank = lambda B=1, L=4, N=128, imp=FAKE, st=FAKE, ws=FAKE, wsb=1 << 20: lib.prefixkv_rank(
