@@ -764,10 +764,20 @@ decode_gqa_kernel(DecodeParams p) {
         }
     }
     if (nsplit > 1) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the partial has been written before the arrival counts
+        // Hand-off of the partial to the last arriver.  Every thread waits until its own partial stores have
+        // been acknowledged (they are device-scope write-through stores, so acknowledged = at the level all
+        // XCDs share), the barrier collects the workgroup, then one thread counts the workgroup in.
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __syncthreads();
         const int i_seg = (sl / p.L) * p.nl + (sl % p.L - p.l0);
+#ifdef PKV_GQA_RELEASE_ACQUIRE
+        // the same hand-off inside the HIP memory model: release on the arrival, acquire in the last arriver
+        if (threadIdx.x == 0)
+            s_last[it & 1] = __hip_atomic_fetch_add(arrive + i_seg * HU + hu, 1, __ATOMIC_ACQ_REL,
+                                                    __HIP_MEMORY_SCOPE_AGENT) == nsplit - 1;
+#else
         if (threadIdx.x == 0) s_last[it & 1] = atomicAdd(arrive + i_seg * HU + hu, 1) == nsplit - 1;
+#endif
         __syncthreads();
         if (s_last[it & 1]) {
             // the partial of piece k sits at the piece's place in the list
@@ -893,6 +903,10 @@ size_t decode_ws_bytes(const pkv_shape& s) {
 template <int D, int G, bool EV>
 static hipError_t launch_gqa_s(DecodeParams p, const pkv_shape& s, int* ws, hipStream_t st) {
     constexpr int W = 4;
+    // Only the 4-wavefront workgroup is instantiated.  8-wavefront workgroups (with 2048-row pieces) were slower
+    // on every workload they were measured on, and one run of that shape ended in a GPU fault whose cause is
+    // not known; the shape must not be used until it is.
+    static_assert(W == 4, "decode_gqa_kernel is validated for 4 wavefronts per workgroup only");
     const GqaLayout lay = gqa_layout(s.B * p.nl, s.H, G, D, s.N);
     p.G = G; p.n_seg = s.B * p.nl; p.S0 = 1024; p.pieces_cap = lay.pieces_cap; p.record_word = lay.record_word; p.partial_word = lay.partial_word;
     p.plan = ws;

@@ -1,28 +1,14 @@
 // Stage 1: KV importance (Sec. 3.2) -- column sums of the causal softmax, averaged over heads.
 //
-// bf16 inputs run on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate) in two passes:
+// bf16 inputs run on the matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate) in ONE kernel that reads
+// the queries and the keys of a head from HBM once (importance_fused_kernel, below): the queries stay in
+// registers, the keys stream through LDS twice -- first for the row log-sum-exp, then for the column sums --
+// and swapping the MFMA operands between the two sweeps gives the layout each of them wants: a lane holds one
+// query and 16 keys in the first (the running max / sum of a row is a scalar per lane), one key and 16 queries
+// in the second (the column sum of a key is a sum inside the lane).
 //
-//  lse_mfma_kernel     query-stationary.  A wavefront keeps 64 query rows (two MFMA tiles) as the B
-//                      operand in registers, key tiles stream through LDS (A operand), and an online
-//                      max/sum per lane yields log sum_{j<=m} exp(scale*q_m.k_j) for every causal row m.
-//  colsum_mfma_kernel  key-stationary.  A wavefront keeps 64 key rows as the A operand in registers,
-//                      query tiles (and their lse) stream through LDS, and exp2(s*c - lse) is added
-//                      into per-key accumulators in registers.  No atomics: the query lanes of a key
-//                      are summed through LDS in a fixed order when the block is finished.
-//
-// Both compute S^T = K.Q^T so that a lane's 16 accumulator values belong to ONE query (column) and 16
-// different keys (rows): the per-query quantity (running max / lse) is a scalar per lane.
-//
-// Work decomposition.  One workgroup (4 wavefronts) owns one (sequence, layer, head) -- or an
-// interleaved share of its blocks when there are few heads -- and walks its 256-row stationary blocks
-// one after the other; for each block the other operand streams through LDS in stages of 128 rows,
-// restricted to the causal side of the diagonal.  All (block, stage) steps of the workgroup form one
-// flat sequence and the streamed tile of the next step is always in flight (global -> registers) while
-// the current one is computed, also across block boundaries, so the start-up latency of a block is
-// paid once per workgroup, not once per block.  Every LDS fragment read feeds two MFMAs.
-//
-// The head mean is a third, tiny kernel that adds the per-head partial sums in head order, so the
-// result is bitwise reproducible.  fp32 inputs (small validation shapes) use plain kernels.
+// The head mean is a second, tiny kernel that adds the per-workgroup partial sums in (head, workgroup)
+// order, so the result is bitwise reproducible.  fp32 inputs (small validation shapes) use plain kernels.
 #include "pkv_common.hpp"
 
 namespace pkv {
@@ -32,21 +18,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kBlock = 256;   // stationary rows per block (4 wavefronts x 64)
 constexpr int kStage = 128;   // streamed rows per LDS stage
-
-struct ImpParams {
-    int B, L, H, Hkv, N, D;
-    int nblocks;               // ceil(N / kBlock)
-    int nsplit;                // workgroups per head; workgroup `split` takes blocks split, split+nsplit, ...
-    long long nwork;           // B*L*H*nsplit
-    const bf16_t* q; Strides qs;
-    const bf16_t* k; Strides ks;
-    const float* scale;        // [L]
-    const float* lse_in;       // [B,L,H,N] natural log (read by the column-sum pass)
-    float* lse_out;            // [B,L,H,N] (written by the lse pass)
-    float* partial;            // [B,L,H,N] per-head column sums
-};
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -63,18 +35,23 @@ __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void glb_void_t;
 
-template <int D> struct Stage {
+template <int D, int WV = 4> struct Stage {
     static constexpr int CPR = D / 8;                 // 16-byte chunks per row
     static constexpr int ROWB = D * 2;                // bytes per row
     static constexpr int RPB = 256 / ROWB;            // rows per 256 bytes (one pass over the 64 banks)
     static constexpr int BYTES = kStage * ROWB;
-    static constexpr int INSTS = BYTES / 1024 / 4;    // load instructions per wavefront (4 wavefronts)
+    static constexpr int PIECES = BYTES / 1024;       // 1 KB pieces of the tile, dealt to the wavefronts in turn
+    static constexpr int INSTS = (PIECES + WV - 1) / WV;
     // Issue the asynchronous copy of rows [row0, row0 + kStage) (clamped to N-1) into `lds`.
     static __device__ __forceinline__ void issue(const bf16_t* base, int64_t ld, int row0, int N,
                                                  unsigned char* lds, int wv, int lane) {
+        // the per-lane address pieces are recomputed at every call (a few integer operations per stage): kept
+        // across a long loop they would occupy two dozen registers
+        asm volatile("" : "+v"(lane));
 #pragma unroll
         for (int i = 0; i < INSTS; ++i) {
-            const int inst = wv * INSTS + i;          // which 1 KB piece of the tile
+            const int inst = i * WV + wv;             // which 1 KB piece of the tile
+            if (PIECES % WV != 0 && inst >= PIECES) break;
             const int L = inst * 64 + lane;           // linear chunk index in LDS
             const int row = L / CPR, pos = L % CPR;
             const int c = pos ^ ((row / RPB) & (CPR - 1));
@@ -133,114 +110,109 @@ __device__ __forceinline__ f32x16 mma_tile(const bf16x8 (&stat)[KS], const bf16x
                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(stat[kk], fr[kk], acc, 0, 0, 0);
     return acc;
 }
-// two tiles that share the streamed fragments, interleaved so that consecutive MFMAs are independent
-template <int KS, bool STREAM_IS_A>
-__device__ __forceinline__ void mma_tile2(const bf16x8 (&stat0)[KS], const bf16x8 (&stat1)[KS],
-                                          const bf16x8 (&fr)[KS], f32x16& acc0, f32x16& acc1) {
-    acc0 = (f32x16){0}; acc1 = (f32x16){0};
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-        if constexpr (STREAM_IS_A) {
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[kk], stat0[kk], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[kk], stat1[kk], acc1, 0, 0, 0);
-        } else {
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stat0[kk], fr[kk], acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stat1[kk], fr[kk], acc1, 0, 0, 0);
-        }
-    }
-}
-
-// The flat (block, stage) walk of one workgroup.  LSE: block i streams keys of stages [0, ceil(min(N,
-// 256(i+1))/128)); COLSUM: block i streams queries of stages [2i, ceil(N/128)).
-template <bool COLSUM>
-struct Walk {
-    int N, nblocks, nsplit, blk, s, s_end;
-    __device__ __forceinline__ int first_stage(int b) const { return COLSUM ? b * (kBlock / kStage) : 0; }
-    __device__ __forceinline__ int end_stage(int b) const {
-        const int rows = COLSUM ? N : min(N, (b + 1) * kBlock);
-        return (rows + kStage - 1) / kStage;
-    }
-    __device__ __forceinline__ void start(int n, int nb, int ns, int split) {
-        N = n; nblocks = nb; nsplit = ns; blk = split; s = first_stage(blk); s_end = end_stage(blk);
-    }
-    __device__ __forceinline__ bool last_stage_of_block() const { return s + 1 >= s_end; }
-    __device__ __forceinline__ bool has_next_block() const { return blk + nsplit < nblocks; }
-    // the step after the current one (the current one again if it is the very last)
-    __device__ __forceinline__ void peek(int& nb, int& ns) const {
-        if (!last_stage_of_block()) { nb = blk; ns = s + 1; }
-        else if (has_next_block()) { nb = blk + nsplit; ns = first_stage(nb); }
-        else { nb = blk; ns = s; }
-    }
-    __device__ __forceinline__ void advance() {
-        if (!last_stage_of_block()) { ++s; }
-        else { blk += nsplit; s = first_stage(blk); s_end = end_stage(blk); }
-    }
+// ---- fused kernel: Q and K are read from HBM once -------------------------------------------------------
+// One workgroup of WV wavefronts owns up to WV PAIRS of 32-query tiles of one (sequence, layer, head): tile i
+// is paired with tile T-1-i, so that every pair -- and therefore every wavefront -- has the same amount of
+// causal work (T+1 tile products per sweep).  With WV = 12 a head of up to 768 positions is ONE workgroup (one
+// per CU, three wavefronts per SIMD: their MFMA chains and softmax phases overlap each other) and its keys pass
+// through LDS exactly once per sweep.  The wavefront keeps its two query tiles in registers for the whole
+// kernel and the keys stream through LDS (128-row stages, asynchronous copies, double-buffered) twice:
+//   sweep 1:  S^T = K.Q^T (a lane holds one query): online max / sum -> lse of the wavefront's 64 rows
+//   sweep 2:  S   = Q.K^T (a lane holds one key):   exp2(c*s - lse) summed over the lane's 32 query rows,
+//             i.e. the column sums of this workgroup's rows; the keys come back from L2 / the last-level cache.
+// Swapping the MFMA operands transposes the product, so the same stationary fragments serve both sweeps.  The
+// column sums of one 128-key stage leave the workgroup once per stage: the wavefronts' values meet in LDS
+// behind the barrier the stage needs anyway and are added in a fixed order (no atomics, bitwise reproducible).
+// The workgroups of one head (long prompts) sit on one XCD next to each other in dispatch order and share the
+// head's keys through that XCD's L2.
+struct FusedParams {
+    int B, L, H, Hkv, N, D;
+    int T;                     // 32-row tiles: ceil(N / 32)
+    int npairs;                // ceil(T / 2)
+    int G;                     // workgroups per head: ceil(npairs / wavefronts per workgroup)
+    long long nheads;          // B*L*H
+    long long chunk;           // logical workgroup ids per XCD (a multiple of G)
+    const bf16_t* q; Strides qs;
+    const bf16_t* k; Strides ks;
+    const float* scale;        // [L]
+    const float* lse_in;       // [B,L,H,N] natural log, or unused
+    float* partial;            // [B*L*H][G][N]: workgroup g's column sums of keys [0, min(N, 32*(T-4g)))
 };
 
-__device__ __forceinline__ void decode_work(const ImpParams& p, long long id, int& b, int& l, int& h, int& split) {
-    split = (int)(id % p.nsplit); id /= p.nsplit;
-    h = (int)(id % p.H); id /= p.H;
-    l = (int)(id % p.L);
-    b = (int)(id / p.L);
-}
-
-template <int D>
-__global__ void __launch_bounds__(256, 2)
-lse_mfma_kernel(ImpParams p) {
+// WV wavefronts per workgroup; OCC wavefronts per SIMD the register allocation must allow.
+template <int D, bool HAS_LSE, int WV, int OCC>
+__global__ void __launch_bounds__(WV * kWave, OCC)
+importance_fused_kernel(FusedParams p) {
     constexpr int KS = D / 16;
-    using St = Stage<D>;
-    // two staging buffers as separate objects: the compiler can then tell that the copy in flight into one
-    // does not alias the fragment reads from the other, and does not wait for it
-    __shared__ __attribute__((aligned(16))) unsigned char s_tileA[St::BYTES];
-    __shared__ __attribute__((aligned(16))) unsigned char s_tileB[St::BYTES];
-    const long long id = xcd_swizzle(blockIdx.x, gridDim.x);
-    if (id >= p.nwork) return;
-    int b, l, h, split;
-    decode_work(p, id, b, l, h, split);
-    if (split >= p.nblocks) return;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    constexpr int NSUB = kStage / 32;
+    using St = Stage<D, WV>;
+    __shared__ __attribute__((aligned(16))) unsigned char s_tile0[St::BYTES];   // even steps
+    __shared__ __attribute__((aligned(16))) unsigned char s_tile1[St::BYTES];   // odd steps
+    __shared__ float s_red[1][WV][NSUB][2][32];           // column sums of one product: [parity][wavefront]
+                                                          // [sub-tile][tile of the pair][key]
+    __shared__ __attribute__((aligned(16))) float s_nl2[WV][2][32];   // -lse (log2 units) of a wavefront's two
+                                                          // tiles by row; -inf for rows that do not exist
+    const long long id = (long long)(blockIdx.x % kXcds) * p.chunk + blockIdx.x / kXcds;
+    const int g = (int)(id % p.G);
+    const long long head = id / p.G;
+    if (head >= p.nheads) return;
+    const int h = (int)(head % p.H), l = (int)((head / p.H) % p.L), b = (int)(head / ((long long)p.H * p.L));
+    // the wavefront index as a scalar: everything derived from it (which tiles exist, which sub-tiles are
+    // needed) is then known to be uniform and branches on it are scalar branches
+    const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bf16_t* qb = p.q + p.qs.b * b + p.qs.l * l + p.qs.h * h;
     const bf16_t* kb = p.k + p.ks.b * b + p.ks.l * l + p.ks.h * (h / (p.H / p.Hkv));
-    float* lse_row = p.lse_out + (((size_t)b * p.L + l) * p.H + h) * p.N;
+    float* part = p.partial + ((size_t)head * p.G + g) * p.N;
     float c = p.scale[l] * kLog2e;
     const bool flip = c < 0.f;
-    c = fabsf(c);
+    c = fmaxf(fabsf(c), 1e-30f);                           // > 0, so that c * (-inf) of a masked entry stays -inf
 
-    Walk<false> w;
-    w.start(p.N, p.nblocks, p.nsplit, split);
-    St::issue(kb, p.ks.n, w.s * kStage, p.N, s_tileA, wv, lane);
-    // Wavefront w owns the 32-row tiles w and 7-w of the block: an early and a late tile, so that the causal
-    // triangle gives every wavefront of a diagonal block the same amount of work.
+    // this wavefront's pair: the early tile tE and the late tile tL (only tL for the middle tile of an odd T)
+    const int pi = WV * g + wv;
+    int tE = pi < p.npairs ? pi : -1, tL = pi < p.npairs ? p.T - 1 - pi : -1;
+    if (tE == tL) tE = -1;
+    const int qlo0 = 32 * tE, qlo1 = 32 * tL;             // negative: tile absent
+    const int klim = min(p.N, 32 * (p.T - WV * g));       // keys this workgroup's rows can see
+    const int S = (klim + kStage - 1) / kStage;           // key stages per sweep
+    // Steps t = t0 .. 2S-1: step t works on key stage t mod S, sweep 1 for t < S and sweep 2 from S on, out of
+    // s_tile{(t - t0) & 1}; the stage of step t+1 is copied into the other buffer meanwhile.
+    const int t0 = HAS_LSE ? S : 0;
+
+    St::issue(kb, p.ks.n, 0, p.N, s_tile0, wv, lane);
     bf16x8 bq[2][KS];
-    int qlo0 = w.blk * kBlock + 32 * wv, qlo1 = w.blk * kBlock + 32 * (7 - wv);
-    load_stationary<D>(bq, qb, p.qs.n, qlo0, qlo1, p.N, lane, flip);
+    load_stationary<D>(bq, qb, p.qs.n, tE < 0 ? 0 : qlo0, tL < 0 ? 0 : qlo1, p.N, lane, flip);
     float mrun[2] = {-INFINITY, -INFINITY}, srun[2] = {0.f, 0.f};
-    wait_async_copies();
-    __syncthreads();
-
-    // one (block, stage) step: compute from `cur` while the next step's keys are copied into `nxt`;
-    // returns true after the last step
-    auto step = [&](const unsigned char* cur, unsigned char* nxt) -> bool {
-        int nb, ns;
-        w.peek(nb, ns);
-        St::issue(kb, p.ks.n, ns * kStage, p.N, nxt, wv, lane);   // (this step's keys again at the very end)
-#pragma unroll
-        for (int j = 0; j < kStage / 32; ++j) {
-            const int n0 = w.s * kStage + 32 * j;          // first key of the sub-tile
-            // tile a holds queries [qlo_a, qlo_a+31]; needed unless all keys of the sub-tile lie above the diagonal
-            const bool need0 = n0 <= qlo0 + 31 && qlo0 < p.N && n0 < p.N;
-            const bool need1 = n0 <= qlo1 + 31 && qlo1 < p.N && n0 < p.N;
-            if (!(need0 || need1)) continue;
-            f32x16 acc0 = {0}, acc1 = {0};
-            bf16x8 fr[KS];
-            load_frags<D>(fr, cur, 32 * j, lane);
-            if (need0 && need1) mma_tile2<KS, true>(bq[0], bq[1], fr, acc0, acc1);
-            else if (need0) acc0 = mma_tile<KS, true>(bq[0], fr);
-            else acc1 = mma_tile<KS, true>(bq[1], fr);
+    if (HAS_LSE) {
+        const float* lse = p.lse_in + (size_t)head * p.N;
+        if (lane < 32) {
 #pragma unroll
             for (int a = 0; a < 2; ++a) {
-                if (!(a == 0 ? need0 : need1)) continue;
-                const f32x16 acc = a == 0 ? acc0 : acc1;
+                const int t = a == 0 ? tE : tL, m = 32 * t + lane;
+                const float v = lse[min(max(m, 0), p.N - 1)];
+                s_nl2[wv][a][lane] = (t >= 0 && m < p.N) ? -v * kLog2e : -INFINITY;   // rows >= N weigh 0
+            }
+        }
+    }
+    wait_async_copies();
+    __syncthreads();
+    int par = 0;
+
+    // sweep 1, one key stage: S^T = K.Q^T, a lane holds one query and 16 keys
+    auto stage1 = [&](const unsigned char* cur, int s) {
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j) {
+            const int n0 = s * kStage + 32 * j;            // first key of the sub-tile
+            const bool need0 = tE >= 0 && n0 <= qlo0 + 31;
+            const bool need1 = tL >= 0 && n0 <= qlo1 + 31;
+            if (!need1) continue;                          // tE < tL: need0 implies need1
+            // the two products of the sub-tile one after the other (16 accumulator registers live at a time: the
+            // other wavefronts of the SIMD fill the gaps of the single MFMA chain)
+            bf16x8 fr[KS];
+            load_frags<D>(fr, cur, 32 * j, lane);
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                if (a == 0 && !need0) continue;
+                const f32x16 acc = mma_tile<KS, true>(bq[a], fr);
                 const int qlo = a == 0 ? qlo0 : qlo1;
                 float mnew, msafe, ps = 0.f;
                 if (n0 + 31 <= qlo) {                      // every key of the sub-tile is visible to every query
@@ -249,180 +221,144 @@ lse_mfma_kernel(ImpParams p) {
                     for (int r = 3; r < 15; r += 2) mx = max3(mx, acc[r], acc[r + 1]);
                     mx = fmaxf(mx, acc[15]);
                     mnew = fmaxf(mrun[a], mx * c);
-                    msafe = mnew;                          // finite: it covers 16 visible keys
+                    msafe = mnew;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) ps += __builtin_amdgcn_exp2f(fmaf(acc[r], c, -msafe));
-                } else {                                   // the sub-tile touches the diagonal: mask key > query
-                    const int dm = qlo + (lane & 31) - n0; // key row i of the sub-tile is visible iff i <= dm
+                } else {                                   // the diagonal sub-tile: mask key > query
+                    int q = lane & 31;
+                    asm volatile("" : "+v"(q));            // keeps the compares out of loop-invariant registers
                     float mx = -INFINITY;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = acc_row(r, lane) <= dm ? fmaxf(mx, acc[r]) : mx;
+                    for (int r = 0; r < 16; ++r) mx = acc_row(r, lane) <= q ? fmaxf(mx, acc[r]) : mx;
                     mnew = fmaxf(mrun[a], mx * c);
                     msafe = mnew == -INFINITY ? 0.f : mnew;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const float e = __builtin_amdgcn_exp2f(fmaf(acc[r], c, -msafe));
-                        ps += acc_row(r, lane) <= dm ? e : 0.f;
+                        ps += acc_row(r, lane) <= q ? e : 0.f;
                     }
                 }
                 srun[a] = srun[a] * __builtin_amdgcn_exp2f(mrun[a] - msafe) + ps;
                 mrun[a] = mnew;
             }
         }
-        wait_async_copies();
-        __syncthreads();
-        if (w.last_stage_of_block()) {
-            // lanes l and l^32 hold the two key halves of the same query
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                const float mo = __shfl_xor(mrun[a], 32, kWave), so = __shfl_xor(srun[a], 32, kWave);
-                const float M = fmaxf(mrun[a], mo);        // finite for m < N: key 0 is visible to every query
-                const float S = srun[a] * __builtin_amdgcn_exp2f(mrun[a] - M) + so * __builtin_amdgcn_exp2f(mo - M);
-                const int m = (a == 0 ? qlo0 : qlo1) + lane;
-                if (lane < 32 && m < p.N) lse_row[m] = (M + __log2f(S)) * kLn2;
-                mrun[a] = -INFINITY; srun[a] = 0.f;
-            }
-            if (!w.has_next_block()) return true;
-            qlo0 = (w.blk + w.nsplit) * kBlock + 32 * wv;
-            qlo1 = (w.blk + w.nsplit) * kBlock + 32 * (7 - wv);
-            load_stationary<D>(bq, qb, p.qs.n, qlo0, qlo1, p.N, lane, flip);
-        }
-        w.advance();
-        return false;
     };
-    while (true) {
-        if (step(s_tileA, s_tileB)) break;
-        if (step(s_tileB, s_tileA)) break;
+    // lse of the wavefront's rows: lanes l and l^32 hold the two key halves of the same query; sweep 2 reads
+    // the result by accumulator row from a wavefront-private LDS row
+    auto finish_lse = [&]() {
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            const float mo = __shfl_xor(mrun[a], 32, kWave), so = __shfl_xor(srun[a], 32, kWave);
+            const float M = fmaxf(mrun[a], mo);
+            const float Ssum = srun[a] * __builtin_amdgcn_exp2f(mrun[a] - M) + so * __builtin_amdgcn_exp2f(mo - M);
+            const int t = a == 0 ? tE : tL;
+            if (lane < 32) s_nl2[wv][a][lane] = (t >= 0 && 32 * t + lane < p.N) ? -(M + __log2f(Ssum)) : -INFINITY;
+        }
+    };
+    // sweep 2, one key stage: S = Q.K^T, a lane holds one key and 16 queries; the column sums of each product
+    // go to the product's own LDS slot
+    auto stage2 = [&](const unsigned char* cur, int s) {
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j) {
+            const int n0 = s * kStage + 32 * j;
+            const bool need0 = tE >= 0 && n0 <= qlo0 + 31;
+            const bool need1 = tL >= 0 && n0 <= qlo1 + 31;
+            float ps0 = 0.f, ps1 = 0.f;
+            if (need1) {
+                bf16x8 fr[KS];
+                load_frags<D>(fr, cur, 32 * j, lane);
+#pragma unroll
+                for (int a = 0; a < 2; ++a) {
+                    if (a == 0 && !need0) continue;
+                    // -lse of accumulator rows 8q + 4*(lane/32) + 0..3: requested before the MFMA chain, so that
+                    // the LDS round trip is over when the chain is
+                    const float4* src = (const float4*)&s_nl2[wv][a][4 * (lane >> 5)];
+                    float nl[16];
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const float4 x = src[2 * q4];
+                        nl[4 * q4] = x.x; nl[4 * q4 + 1] = x.y; nl[4 * q4 + 2] = x.z; nl[4 * q4 + 3] = x.w;
+                    }
+                    const f32x16 acc = mma_tile<KS, false>(bq[a], fr);
+                    const int qlo = a == 0 ? qlo0 : qlo1;
+                    float ps = 0.f;
+                    if (n0 + 31 <= qlo) {                  // every key of the sub-tile is visible to every query
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) ps += __builtin_amdgcn_exp2f(fmaf(acc[r], c, nl[r]));
+                    } else {                               // the diagonal sub-tile: mask key > query
+                        int key = lane & 31;
+                        asm volatile("" : "+v"(key));      // keeps the compares out of loop-invariant registers
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const float pr = __builtin_amdgcn_exp2f(fmaf(acc[r], c, nl[r]));
+                            ps += key <= acc_row(r, lane) ? pr : 0.f;
+                        }
+                    }
+                    if (a == 0) ps0 = ps; else ps1 = ps;
+                }
+            }
+            // lanes l and l+32 hold the two query halves of the same key
+            const auto s0 = __builtin_amdgcn_permlane32_swap(__float_as_uint(ps0), __float_as_uint(ps0), false, false);
+            const auto s1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(ps1), __float_as_uint(ps1), false, false);
+            const float t0v = __uint_as_float(s0[0]) + __uint_as_float(s0[1]);
+            const float t1v = __uint_as_float(s1[0]) + __uint_as_float(s1[1]);
+            s_red[par][wv][j][lane >> 5][lane & 31] = lane < 32 ? t0v : t1v;
+        }
+    };
+    auto step = [&](const unsigned char* cur, unsigned char* nxt, int t) {
+        if (t + 1 < 2 * S) St::issue(kb, p.ks.n, ((t + 1) % S) * kStage, p.N, nxt, wv, lane);
+        const int s = t >= S ? t - S : t;
+        if (t < S) {
+            stage1(cur, s);
+            if (t == S - 1) finish_lse();
+            wait_async_copies();
+            __syncthreads();
+        } else {
+            stage2(cur, s);
+            wait_async_copies();
+            __syncthreads();
+            if (threadIdx.x < kStage) {
+                const int sub = threadIdx.x >> 5, c32 = threadIdx.x & 31;
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < WV; ++w) sum += s_red[par][w][sub][0][c32] + s_red[par][w][sub][1][c32];
+                const int n = s * kStage + threadIdx.x;
+                if (n < klim) part[n] = sum;
+            }
+            __syncthreads();                               // single s_red buffer: read before the next stage writes
+        }
+    };
+    for (int t = t0; t < 2 * S; t += 2) {
+        step(s_tile0, s_tile1, t);
+        if (t + 1 < 2 * S) step(s_tile1, s_tile0, t + 1);
     }
 }
 
-template <int D>
-__global__ void __launch_bounds__(256, 2)
-colsum_mfma_kernel(ImpParams p) {
-    constexpr int KS = D / 16;
-    using St = Stage<D>;
-    constexpr int RED_BYTES = 4 * 64 * 33 * 4;             // wavefront x 64 keys x 32 query lanes (+1 pad)
-    constexpr int BUF = St::BYTES > RED_BYTES ? St::BYTES : RED_BYTES;   // a consumed staging buffer doubles as
-                                                                          // the reduction buffer
-    // separate objects, so that the copy in flight into one buffer is known not to alias reads of the other
-    __shared__ __attribute__((aligned(16))) unsigned char s_tileA[BUF];
-    __shared__ __attribute__((aligned(16))) unsigned char s_tileB[BUF];
-    __shared__ __attribute__((aligned(16))) float s_lseA[kStage];
-    __shared__ __attribute__((aligned(16))) float s_lseB[kStage];
-    const long long id = xcd_swizzle(blockIdx.x, gridDim.x);
-    if (id >= p.nwork) return;
-    int b, l, h, split;
-    decode_work(p, id, b, l, h, split);
-    if (split >= p.nblocks) return;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const bf16_t* qb = p.q + p.qs.b * b + p.qs.l * l + p.qs.h * h;
-    const bf16_t* kb = p.k + p.ks.b * b + p.ks.l * l + p.ks.h * (h / (p.H / p.Hkv));
-    const float* lse = p.lse_in + (((size_t)b * p.L + l) * p.H + h) * p.N;
-    float* part_row = p.partial + (((size_t)b * p.L + l) * p.H + h) * p.N;
-    float c = p.scale[l] * kLog2e;
-    const bool flip = c < 0.f;
-    c = fabsf(c);
-    Walk<true> w;
-    w.start(p.N, p.nblocks, p.nsplit, split);
-    // the lse of the staged query rows travels the same way: 4-byte copies, lane i -> dst[64*wv + i]
-    auto issue_lse = [&](int stage, float* dst) {
-        if (wv < kStage / 64) {
-            int mrow = stage * kStage + 64 * wv + lane;
-            mrow = mrow < p.N ? mrow : p.N - 1;
-            __builtin_amdgcn_global_load_lds((glb_void_t*)(lse + mrow), (lds_void_t*)(dst + 64 * wv), 4, 0, 0);
+// importance[b,l,n] = (1/H) * sum_h sum_g partial[b,l,h,g,n] over the workgroups g whose rows see key n,
+// added in (h, g) order.
+__global__ void head_mean_fused_kernel(int H, int G, int N, int T, int WV, long long total, const float* __restrict__ partial,
+                                       float* __restrict__ importance) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const long long bl = i / N;
+    const int n = (int)(i % N);
+    // workgroup g covers keys below 32*(T - WV*g): g <= (T - 1 - n/32) / WV
+    const int gmax = min(G - 1, (T - 1 - n / 32) / WV);
+    const float* src = partial + (size_t)bl * H * G * N + n;
+    float acc = 0.f;
+    for (int h = 0; h < H; ++h) {
+        const float* sh = src + (size_t)h * G * N;
+        int g = 0;
+        for (; g + 4 <= gmax + 1; g += 4) {
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = sh[(size_t)(g + j) * N];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc += v[j];
         }
-    };
-    St::issue(qb, p.qs.n, w.s * kStage, p.N, s_tileA, wv, lane);
-    issue_lse(w.s, s_lseA);
-    // Wavefront w owns the 32-row key tiles w and 7-w of the block (balanced causal work, as in the lse pass).
-    bf16x8 ak[2][KS];
-    int klo0 = w.blk * kBlock + 32 * wv, klo1 = w.blk * kBlock + 32 * (7 - wv);
-    load_stationary<D>(ak, kb, p.ks.n, klo0, klo1, p.N, lane, flip);
-    float col[2][16];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) col[a][r] = 0.f;
-    wait_async_copies();
-    __syncthreads();
-
-    // one (block, stage) step: compute from `cur` while the next step's queries and lse are copied into `nxt`;
-    // returns true after the last step
-    auto step = [&](unsigned char* cur, const float* cur_lse, unsigned char* nxt, float* nxt_lse) -> bool {
-        int nb, ns;
-        w.peek(nb, ns);
-        St::issue(qb, p.qs.n, ns * kStage, p.N, nxt, wv, lane);   // (this step's rows again at the very end)
-        issue_lse(ns, nxt_lse);
-#pragma unroll
-        for (int j = 0; j < kStage / 32; ++j) {
-            const int mt = w.s * kStage + 32 * j;          // first query of the sub-tile
-            // tile a holds keys [klo_a, klo_a+31]; needed unless all queries of the sub-tile lie before its keys
-            const bool need0 = mt + 31 >= klo0 && klo0 < p.N && mt < p.N;
-            const bool need1 = mt + 31 >= klo1 && klo1 < p.N && mt < p.N;
-            if (!need0) continue;                          // klo0 <= klo1: need1 implies need0
-            f32x16 acc0 = {0}, acc1 = {0};
-            bf16x8 fr[KS];
-            load_frags<D>(fr, cur, 32 * j, lane);
-            if (need1) mma_tile2<KS, false>(ak[0], ak[1], fr, acc0, acc1);
-            else acc0 = mma_tile<KS, false>(ak[0], fr);
-            const int m = mt + (lane & 31);
-            // rows >= N carry +inf: their weight is exp2(-inf) = 0
-            const float l2 = m < p.N ? cur_lse[32 * j + (lane & 31)] * kLog2e : INFINITY;
-#pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                if (a == 1 && !need1) continue;
-                const f32x16 acc = a == 0 ? acc0 : acc1;
-                const int klo = a == 0 ? klo0 : klo1;
-                if (mt >= klo + 31) {                      // every query of the sub-tile sees every key of the tile
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) col[a][r] += __builtin_amdgcn_exp2f(fmaf(acc[r], c, -l2));
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float pr = __builtin_amdgcn_exp2f(fmaf(acc[r], c, -l2));
-                        col[a][r] += (klo + acc_row(r, lane) > m) ? 0.f : pr;
-                    }
-                }
-            }
-        }
-        wait_async_copies();
-        __syncthreads();
-        if (w.last_stage_of_block()) {
-            // The block is complete.  Fetch the next block's keys first (independent of the reduction), then
-            // sum the 32 query lanes of every key through the staging buffer that was just consumed.
-            const bool more = w.has_next_block();
-            const int kold0 = klo0, kold1 = klo1;
-            if (more) {
-                klo0 = (w.blk + w.nsplit) * kBlock + 32 * wv;
-                klo1 = (w.blk + w.nsplit) * kBlock + 32 * (7 - wv);
-                load_stationary<D>(ak, kb, p.ks.n, klo0, klo1, p.N, lane, flip);
-            }
-            float* red = (float*)cur + wv * 64 * 33;
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    red[(32 * a + acc_row(r, lane)) * 33 + (lane & 31)] = col[a][r];
-                    col[a][r] = 0.f;
-                }
-            __syncthreads();
-            {
-                float sum = 0.f;
-#pragma unroll
-                for (int j = 0; j < 32; ++j) sum += red[lane * 33 + j];
-                const int n = (lane < 32 ? kold0 : kold1 - 32) + lane;   // red rows 0..31 = tile 0, 32..63 = tile 1
-                if (n < p.N) part_row[n] = sum;
-            }
-            __syncthreads();                               // `cur` becomes a copy target in the next step
-            if (!more) return true;
-        }
-        w.advance();
-        return false;
-    };
-    while (true) {
-        if (step(s_tileA, s_lseA, s_tileB, s_lseB)) break;
-        if (step(s_tileB, s_lseB, s_tileA, s_lseA)) break;
+        for (; g <= gmax; ++g) acc += sh[(size_t)g * N];
     }
+    importance[i] = acc / (float)H;
 }
 
 // importance[b,l,n] = (1/H) * sum_h partial[b,l,h,n], heads added in order.
@@ -503,9 +439,20 @@ __global__ void colsum_naive_kernel(NaiveParams p) {
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// wavefronts per workgroup of the fused kernel: 12 (one workgroup per CU, three wavefronts per SIMD) so that a
+// head of up to 768 positions is one workgroup and its keys pass through LDS once per sweep
+constexpr int kFusedWaves = 12;
+constexpr int kFusedOcc = 1;
+static int fused_groups(int N) {
+    const int T = (N + 31) / 32, npairs = (T + 1) / 2;
+    return (npairs + kFusedWaves - 1) / kFusedWaves;
+}
+
 size_t importance_ws_bytes(const pkv_shape& s, bool has_lse) {
     const size_t per = align_up((size_t)s.B * s.L * s.H * s.N * sizeof(float), 256);
-    return per * (has_lse ? 1 : 2);
+    if (s.dtype == PKV_F32) return per * (has_lse ? 1 : 2);
+    // bf16: one row of column sums per (head, workgroup of the head)
+    return align_up((size_t)s.B * s.L * s.H * fused_groups(s.N) * s.N * sizeof(float), 256);
 }
 
 hipError_t launch_importance(const pkv_shape& s, const void* q, Strides qs, const void* k, Strides ks,
@@ -513,10 +460,11 @@ hipError_t launch_importance(const pkv_shape& s, const void* q, Strides qs, cons
                              hipStream_t st) {
     const size_t per = align_up((size_t)s.B * s.L * s.H * s.N * sizeof(float), 256);
     float* partial = (float*)ws;
-    float* lse_ws = (float*)((unsigned char*)ws + per);
     const long long rows = (long long)s.B * s.L * s.H * s.N;
+    const long long total = (long long)s.B * s.L * s.N;
     hipError_t e;
     if (s.dtype == PKV_F32) {
+        float* lse_ws = (float*)((unsigned char*)ws + per);
         NaiveParams p{s.B, s.L, s.H, s.Hkv, s.N, s.D, (const float*)q, qs, (const float*)k, ks, scale,
                       lse ? lse : lse_ws, lse_ws, partial};
         const int nb = (int)((rows + 127) / 128);
@@ -526,30 +474,32 @@ hipError_t launch_importance(const pkv_shape& s, const void* q, Strides qs, cons
         }
         hipLaunchKernelGGL(colsum_naive_kernel, dim3(nb), dim3(128), 0, st, p);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-    } else {
-        ImpParams p;
-        p.B = s.B; p.L = s.L; p.H = s.H; p.Hkv = s.Hkv; p.N = s.N; p.D = s.D;
-        p.nblocks = (s.N + kBlock - 1) / kBlock;
-        // one workgroup per head; with few heads, split a head's blocks over several workgroups
-        const long long heads = (long long)s.B * s.L * s.H;
-        long long want = (1024 + heads - 1) / heads;
-        p.nsplit = (int)(want < 1 ? 1 : (want > p.nblocks ? p.nblocks : want));
-        p.nwork = heads * p.nsplit;
-        p.q = (const bf16_t*)q; p.qs = qs; p.k = (const bf16_t*)k; p.ks = ks; p.scale = scale;
-        p.lse_in = lse ? lse : lse_ws; p.lse_out = lse_ws; p.partial = partial;
-        const unsigned nblk = (unsigned)((p.nwork + kXcds - 1) / kXcds * kXcds);
-        if (!lse) {
-            if (s.D == 128) hipLaunchKernelGGL(lse_mfma_kernel<128>, dim3(nblk), dim3(256), 0, st, p);
-            else hipLaunchKernelGGL(lse_mfma_kernel<64>, dim3(nblk), dim3(256), 0, st, p);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-        }
-        if (s.D == 128) hipLaunchKernelGGL(colsum_mfma_kernel<128>, dim3(nblk), dim3(256), 0, st, p);
-        else hipLaunchKernelGGL(colsum_mfma_kernel<64>, dim3(nblk), dim3(256), 0, st, p);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL(head_mean_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s.H, s.N,
+                           total, partial, importance);
+        return hipGetLastError();
     }
-    const long long total = (long long)s.B * s.L * s.N;
-    hipLaunchKernelGGL(head_mean_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s.H, s.N,
-                       total, partial, importance);
+    FusedParams p;
+    p.B = s.B; p.L = s.L; p.H = s.H; p.Hkv = s.Hkv; p.N = s.N; p.D = s.D;
+    p.T = (s.N + 31) / 32;
+    p.npairs = (p.T + 1) / 2;
+    p.G = fused_groups(s.N);
+    p.nheads = (long long)s.B * s.L * s.H;
+    p.chunk = (p.nheads + kXcds - 1) / kXcds * p.G;          // whole heads per XCD
+    p.q = (const bf16_t*)q; p.qs = qs; p.k = (const bf16_t*)k; p.ks = ks; p.scale = scale;
+    p.lse_in = lse; p.partial = partial;
+    const long long nblk = p.chunk * kXcds;
+    if (nblk > 0x7fffffffll) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)nblk), block(kFusedWaves * kWave);
+    if (lse) {
+        if (s.D == 128) hipLaunchKernelGGL((importance_fused_kernel<128, true, kFusedWaves, kFusedOcc>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((importance_fused_kernel<64, true, kFusedWaves, kFusedOcc>), grid, block, 0, st, p);
+    } else {
+        if (s.D == 128) hipLaunchKernelGGL((importance_fused_kernel<128, false, kFusedWaves, kFusedOcc>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((importance_fused_kernel<64, false, kFusedWaves, kFusedOcc>), grid, block, 0, st, p);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(head_mean_fused_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s.H, p.G, s.N,
+                       p.T, kFusedWaves, total, partial, importance);
     return hipGetLastError();
 }
 

@@ -30,10 +30,15 @@ def test_library_exports_every_declared_symbol():
 
 def test_workspace_queries():
     dt = P.PKV_BF16
-    per = 1 * 32 * 32 * 680 * 4
-    per = (per + 255) // 256 * 256
-    assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 32, 32, 32, 680, 128, dt) == 2 * per
+    # bf16: one row of N column sums per (head, workgroup of the head); a workgroup holds 12 pairs of 32-row
+    # tiles, so 680 positions (22 tiles, 11 pairs) are one workgroup and 8192 positions (128 pairs) are 11
+    per = (1 * 32 * 32 * 680 * 4 + 255) // 256 * 256
+    assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 32, 32, 32, 680, 128, dt) == per
     assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 32, 32, 32, 680, 128, dt, has_lse=True) == per
+    assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 4, 32, 32, 8, 8192, 128, dt) == 4 * 32 * 32 * 11 * 8192 * 4
+    f32 = (1 * 4 * 2 * 128 * 4 + 255) // 256 * 256
+    assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 4, 2, 2, 128, 64, P.PKV_F32) == 2 * f32
+    assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 4, 2, 2, 128, 64, P.PKV_F32, has_lse=True) == f32
     assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 32, 32, 32, 680, 128, dt) == 2 * 32 * 4
     assert P.prefixkv_workspace_bytes(Bd.OP_DECODE, 1, 32, 32, 32, 680, 128, dt) == 0
     # invalid shapes give 0
