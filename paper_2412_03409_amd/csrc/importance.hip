@@ -148,18 +148,18 @@ importance_fused_kernel(FusedParams p) {
     using St = Stage<D, WV>;
     __shared__ __attribute__((aligned(16))) unsigned char s_tile0[St::BYTES];   // even steps
     __shared__ __attribute__((aligned(16))) unsigned char s_tile1[St::BYTES];   // odd steps
-    __shared__ float s_red[1][WV][NSUB][2][32];           // column sums of one product: [parity][wavefront]
-                                                          // [sub-tile][tile of the pair][key]
+    __shared__ float s_red[2][WV][NSUB][32];              // column sums of a wavefront's rows:
+                                                          // [parity][wavefront][sub-tile][key]
     __shared__ __attribute__((aligned(16))) float s_nl2[WV][2][32];   // -lse (log2 units) of a wavefront's two
                                                           // tiles by row; -inf for rows that do not exist
+    // the wavefront index as a scalar: everything derived from it (which tiles exist, which sub-tiles are
+    // needed) is then known to be uniform and branches on it are scalar branches
+    const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long long id = (long long)(blockIdx.x % kXcds) * p.chunk + blockIdx.x / kXcds;
     const int g = (int)(id % p.G);
     const long long head = id / p.G;
     if (head >= p.nheads) return;
     const int h = (int)(head % p.H), l = (int)((head / p.H) % p.L), b = (int)(head / ((long long)p.H * p.L));
-    // the wavefront index as a scalar: everything derived from it (which tiles exist, which sub-tiles are
-    // needed) is then known to be uniform and branches on it are scalar branches
-    const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bf16_t* qb = p.q + p.qs.b * b + p.qs.l * l + p.qs.h * h;
     const bf16_t* kb = p.k + p.ks.b * b + p.ks.l * l + p.ks.h * (h / (p.H / p.Hkv));
     float* part = p.partial + ((size_t)head * p.G + g) * p.N;
@@ -298,11 +298,9 @@ importance_fused_kernel(FusedParams p) {
                 }
             }
             // lanes l and l+32 hold the two query halves of the same key
-            const auto s0 = __builtin_amdgcn_permlane32_swap(__float_as_uint(ps0), __float_as_uint(ps0), false, false);
-            const auto s1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(ps1), __float_as_uint(ps1), false, false);
-            const float t0v = __uint_as_float(s0[0]) + __uint_as_float(s0[1]);
-            const float t1v = __uint_as_float(s1[0]) + __uint_as_float(s1[1]);
-            s_red[par][wv][j][lane >> 5][lane & 31] = lane < 32 ? t0v : t1v;
+            const float ps = ps0 + ps1;
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(ps), __float_as_uint(ps), false, false);
+            if (lane < 32) s_red[par][wv][j][lane] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
         }
     };
     auto step = [&](const unsigned char* cur, unsigned char* nxt, int t) {
@@ -321,11 +319,11 @@ importance_fused_kernel(FusedParams p) {
                 const int sub = threadIdx.x >> 5, c32 = threadIdx.x & 31;
                 float sum = 0.f;
 #pragma unroll
-                for (int w = 0; w < WV; ++w) sum += s_red[par][w][sub][0][c32] + s_red[par][w][sub][1][c32];
+                for (int w = 0; w < WV; ++w) sum += s_red[par][w][sub][c32];
                 const int n = s * kStage + threadIdx.x;
                 if (n < klim) part[n] = sum;
             }
-            __syncthreads();                               // single s_red buffer: read before the next stage writes
+            par ^= 1;
         }
     };
     for (int t = t0; t < 2 * S; t += 2) {
