@@ -129,6 +129,11 @@ typedef struct {
     int32_t fixup;         /* 0 / 1 */
 } pkv_select_params;
 
+/*   ws [dev]: prefixkv_workspace_bytes(PKV_OP_SELECT, shape, 0) bytes; contents on entry and after the
+ *   call are unspecified.  It holds one status word per (sequence, layer) and, per layer, the prefix
+ *   lengths at the 255 ratios t/256: the first eight bisection steps of Algorithm 1 can only ask for
+ *   those, so the search serves them from that table (same lengths, same p, same iteration count as
+ *   walking the cumulative sums) and reads the sums only from the ninth step on. */
 int prefixkv_select(int B, int L, int N, const float *importance /* [dev] [B,L,N] */,
                     const pkv_select_params *params /* [host] */, int32_t *order, uint64_t *cum,
                     float *prefix, int32_t *lengths, double *p_out, int32_t *iters,
@@ -137,7 +142,9 @@ int prefixkv_select(int B, int L, int N, const float *importance /* [dev] [B,L,N
 
 /* ---- prefixkv_select for callers that cannot allocate device memory at all and therefore have no
  * workspace to pass: code under HIP graph capture, tight serving loops, harnesses that forbid
- * hipMalloc.  Same arguments, same kernels and bit-identical results as prefixkv_select; the scratch
+ * hipMalloc.  Same arguments, same kernels and bit-identical results as prefixkv_select, except that
+ * the search takes every bisection step on the cumulative sums (no table of tabulated ratios, which
+ * would need 1 KB per layer); the scratch
  * (one status word per (sequence, layer)) is a fixed array built into the library instead of `ws`:
  * 65536 words = 256 KB, which every GPU the library runs on holds until the process ends.
  *   B * L <= prefixkv_static_scratch_segments() (= 65536), else PKV_ERR_WORKSPACE, nothing enqueued.

@@ -156,6 +156,12 @@ def prefixkv_workspace_bytes(op: int, B, L, H, Hkv, N, D, dtype, has_lse: bool =
     return int(load().prefixkv_workspace_bytes(op, C.byref(s), int(has_lse)))
 
 
+def select_workspace_bytes(B: int, L: int, N: int) -> int:
+    # stages 2 and 3 do not depend on the head geometry: any valid one serves for the size query
+    s = _shape(B, L, 1, 1, N, 128, PKV_BF16)
+    return int(load().prefixkv_workspace_bytes(OP_SELECT, C.byref(s), 0))
+
+
 def prefixkv_cache_tokens_upper_bound(B: int, budget_tokens: int, L: int, decode_capacity: int) -> int:
     return int(load().prefixkv_cache_tokens_upper_bound(B, budget_tokens, L, decode_capacity))
 
@@ -241,7 +247,7 @@ def prefixkv_select(importance: torch.Tensor, budget_tokens: int, tol_tokens: in
             raw_total=torch.empty(B, dtype=torch.int64, device=dev),
             status=torch.empty(B, dtype=torch.int32, device=dev))
     prm = _SelectParams(int(budget_tokens), int(tol_tokens), int(max_iters), int(bool(fixup)))
-    w = _ws(B * L * 4, dev, ws)
+    w = _ws(select_workspace_bytes(B, L, N), dev, ws)
     rc = load().prefixkv_select(B, L, N, _ptr(importance), C.byref(prm), _ptr(out.order), _ptr(out.cum),
                                 _ptr(out.prefix), _ptr(out.lengths), _ptr(out.p), _ptr(out.iters),
                                 _ptr(out.raw_total), _ptr(out.status), _ptr(w),
@@ -294,7 +300,7 @@ def prefixkv_rank(importance: torch.Tensor, want_prefix: bool = True, out: Optio
             cum=torch.empty((B, L, N), dtype=torch.int64, device=dev),
             prefix=torch.empty((B, L, N), dtype=torch.float32, device=dev) if want_prefix else None,
             status=torch.empty(B, dtype=torch.int32, device=dev))
-    w = _ws(B * L * 4, dev, ws)
+    w = _ws(select_workspace_bytes(B, L, N), dev, ws)
     rc = load().prefixkv_rank(B, L, N, _ptr(importance), _ptr(out.order), _ptr(out.cum), _ptr(out.prefix),
                               _ptr(out.status), _ptr(w), w.numel() * w.element_size(), _stream())
     if rc != 0:

@@ -49,7 +49,8 @@ hipError_t launch_prefill_attn(const pkv_shape& s, const void* q, Strides qs, co
 size_t select_ws_bytes(int B, int L, int N);
 hipError_t launch_select(int B, int L, int N, const float* importance, const pkv_select_params& p,
                          int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
-                         int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, hipStream_t st);
+                         int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, bool with_table,
+                         hipStream_t st);
 
 int select_static_max_segments();
 hipError_t launch_select_static(int B, int L, int N, const float* importance, const pkv_select_params& p,

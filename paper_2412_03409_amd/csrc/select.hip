@@ -1,10 +1,13 @@
 // Stages 2 and 3 of the PrefixKV hot path.
 //
 //  sort_prefix_kernel  one workgroup per (sequence, layer): the priority sequence of Sec. 3.2 (positions
-//                      by importance, descending) by a bitonic sort of 64-bit keys held in LDS, then the
-//                      cumulative priority as an exact integer scan of fixed-point weights.
+//                      by importance, descending) by a bitonic sort of 64-bit keys -- in registers and
+//                      wavefront shuffles wherever a stage stays inside a wavefront, through LDS otherwise --
+//                      then the cumulative priority as an exact integer scan of fixed-point weights, and the
+//                      layer's prefix lengths at the ratios t/256 (the first eight steps of the search).
 //  search_kernel       one workgroup per sequence, 32 lanes per layer: Algorithm 1 (Sec. 3.3) runs to
-//                      completion on the device, followed by the proportional rescale to the budget.
+//                      completion on the device -- eight steps on the summed tables, the rest on the
+//                      cumulative sums -- followed by the proportional rescale to the budget.
 //
 // Everything that decides an index or a length is integer or a single fp64 product + compare, so the
 // results do not depend on scan order or launch shape.
@@ -37,60 +40,126 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int m) {
+    uint32_t lo = __shfl_xor((uint32_t)v, m, kWave);
+    uint32_t hi = __shfl_xor((uint32_t)(v >> 32), m, kWave);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// The stages of bitonic merge step k whose partner distance is below 64*E, on keys held in registers: a
+// wavefront owns an aligned block of 64*E keys, register e of lane l is position base + 64*e + l.  Distances
+// of 64 and more pair two registers of one lane, smaller ones pair two lanes (one shuffle per key).
+template <int E>
+__device__ __forceinline__ void wave_stages(uint64_t (&r)[E], int k, int base, int lane) {
+#pragma unroll
+    for (int je = E / 2; je >= 1; je >>= 1) {           // partner distance 64*je, between registers
+        if (64 * je >= k) continue;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if (e & je) continue;
+            const bool up = ((base + 64 * e) & k) == 0; // lane < 64 <= k/2: the lane bits do not reach bit k
+            const uint64_t a = r[e], b = r[e | je];
+            const bool sw = (a > b) == up;
+            r[e] = sw ? b : a;
+            r[e | je] = sw ? a : b;
+        }
+    }
+#pragma unroll
+    for (int j = 32; j >= 1; j >>= 1) {                 // between lanes
+        if (j >= k) continue;
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const uint64_t a = r[e], b = shfl_xor_u64(a, j);
+            const bool up = ((base + 64 * e + lane) & k) == 0;
+            const bool keep_min = ((lane & j) == 0) == up;
+            r[e] = (a < b) == keep_min ? a : b;
+        }
+    }
+}
+
+// Ratios served from a table: p = (t + 1) / 2^kTabBits, t = 0 .. kTabN - 1 (rows of kTabN + 1 ints)
+constexpr int kTabBits = 8;
+constexpr int kTabN = (1 << kTabBits) - 1;
+
 // Sort key: high word = ~bits(importance) (non-negative floats order like their bit patterns, so the
 // complement orders them descending), low word = position (ascending among equal values).
 // Padding keys are all ones: they sort last and decode to weight 0.
+// P = E * ns keys, ns = the sorting threads (whole wavefronts, the first of the workgroup); a bitonic network,
+// ascending.  Merge steps up to 64*E keys and the tail of every longer one run in registers inside a
+// wavefront, without a barrier; only the stages that pair keys of different wavefronts go through LDS.
+template <int E>
 __global__ void sort_prefix_kernel(int N, int P, const float* __restrict__ importance,
                                    int32_t* __restrict__ order, uint64_t* __restrict__ cum,
-                                   float* __restrict__ prefix, int32_t* __restrict__ seg_status) {
+                                   float* __restrict__ prefix, int32_t* __restrict__ seg_status,
+                                   int32_t* __restrict__ ktab) {
     extern __shared__ uint64_t skey[];          // P keys, then reused for the scan
     __shared__ uint64_t wave_tot[16];
     __shared__ int s_flags;
-    const int tid = threadIdx.x, nt = blockDim.x;
+    const int tid = threadIdx.x, nt = P / E;    // nt sorting threads; a larger workgroup idles the rest
+    const int lane = tid & (kWave - 1), wv = tid / kWave;
+    const bool sorter = tid < nt;
     const size_t seg = blockIdx.x;
     const float* imp = importance + seg * (size_t)N;
     if (tid == 0) s_flags = 0;
-    __syncthreads();
 
     int flags = 0;
-    for (int i = tid; i < P; i += nt) {
-        uint64_t key = ~0ull;
-        if (i < N) {
-            uint32_t bits = __float_as_uint(imp[i]);
-            if ((bits & 0x7f800000u) == 0x7f800000u) flags |= PKV_DEV_NONFINITE;
-            else if (bits == 0x80000000u) bits = 0;  // -0.0 counts as +0.0
-            else if (bits & 0x80000000u) flags |= PKV_DEV_NEGATIVE;
-            key = ((uint64_t)(~bits) << 32) | (uint32_t)i;
+    const int wbase = wv * (kWave * E);
+    uint64_t r[E];
+    if (sorter) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const int i = wbase + kWave * e + lane;
+            uint64_t key = ~0ull;
+            if (i < N) {
+                uint32_t bits = __float_as_uint(imp[i]);
+                if ((bits & 0x7f800000u) == 0x7f800000u) flags |= PKV_DEV_NONFINITE;
+                else if (bits == 0x80000000u) bits = 0;  // -0.0 counts as +0.0
+                else if (bits & 0x80000000u) flags |= PKV_DEV_NEGATIVE;
+                key = ((uint64_t)(~bits) << 32) | (uint32_t)i;
+            }
+            r[e] = key;
         }
-        skey[i] = key;
+        const int kw = P < kWave * E ? P : kWave * E;
+        for (int k = 2; k <= kw; k <<= 1) wave_stages<E>(r, k, wbase, lane);
     }
+    __syncthreads();                                      // s_flags = 0 is visible
     if (flags) atomicOr(&s_flags, flags);
-    __syncthreads();
-
-    // bitonic network, ascending
-    for (int k = 2; k <= P; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = tid; t < (P >> 1); t += nt) {
+    for (int k = 2 * kWave * E; k <= P; k <<= 1) {
+        if (sorter) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) skey[wbase + kWave * e + lane] = r[e];
+        }
+        __syncthreads();
+        for (int j = k >> 1; j >= kWave * E; j >>= 1) {
+            for (int t = tid; t < (P >> 1); t += blockDim.x) {
                 const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
                 const int x = i | j;
                 const uint64_t a = skey[i], b = skey[x];
                 const bool up = (i & k) == 0;
                 if ((a > b) == up) { skey[i] = b; skey[x] = a; }
             }
-            // A wavefront's 64 pairs of a stage with partner distance j <= 64 lie in one aligned block of
-            // 128 keys, the same block for all such stages: only a stage that reaches further (or is
-            // followed by one that does) has to meet the other wavefronts.
-            const int jn = j > 1 ? (j >> 1) : k;          // partner distance of the next stage
-            if (j > kWave || jn > kWave) __syncthreads(); else wave_sync();
+            __syncthreads();
         }
+        if (sorter) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) r[e] = skey[wbase + kWave * e + lane];
+            wave_stages<E>(r, k, wbase, lane);
+        }
+        // the next write of skey (next k, or the sorted keys below) is to this wavefront's own block, which
+        // only this wavefront has read since the last barrier
     }
+    if (sorter) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) skey[wbase + kWave * e + lane] = r[e];
+    }
+    __syncthreads();
 
     // fixed-point weights and their inclusive scan; each thread owns E consecutive sorted entries
-    const int E = P / nt;  // P and nt are powers of two with P >= nt
-    const int base = tid * E;
+    const int base = tid * E;                 // threads beyond the sorting ones own nothing
     uint64_t local = 0;
     const double two36 = 68719476736.0;
-    for (int e = 0; e < E; ++e) {
+    flags = 0;                                // what the key pass found is in s_flags already
+    for (int e = 0; e < (sorter ? E : 0); ++e) {
         const uint64_t key = skey[base + e];
         const float v = __uint_as_float(~(uint32_t)(key >> 32));
         const double wd = floor((double)v * two36);
@@ -103,7 +172,6 @@ __global__ void sort_prefix_kernel(int N, int P, const float* __restrict__ impor
         skey[base + e] = local;  // thread-local inclusive sums, rebased below
     }
     // scan of the thread totals: within the wave by shuffles, across waves through LDS
-    const int lane = tid & (kWave - 1), wv = tid / kWave;
     uint64_t incl = local;
     for (int d = 1; d < kWave; d <<= 1) {
         const uint64_t up = shfl_up_u64(incl, d);
@@ -127,10 +195,25 @@ __global__ void sort_prefix_kernel(int N, int P, const float* __restrict__ impor
         if (j < N) {
             const uint64_t c = sat_add(excl, skey[j]);
             cum[seg * (size_t)N + j] = c;
+            skey[j] = c;
             if (prefix && total) prefix[seg * (size_t)N + j] = (float)((double)c / dtotal);
         }
     }
     __syncthreads();
+    // The first kTabBits steps of Algorithm 1 (Sec. 3.3) can only ask for the ratios t / 2^kTabBits: the prefix
+    // length of this layer at each of them, from the row while it is still in LDS.  The search adds the
+    // layers' tables up and walks those steps without touching the rows.
+    if (ktab) {
+        for (int t = tid; t < kTabN; t += blockDim.x) {
+            const double thr = __dmul_rn((double)(t + 1) * (1.0 / (double)(kTabN + 1)), dtotal);
+            int lo = 1, hi = N;                           // smallest k in [1, N] with C_k >= thr (C_N >= thr)
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if ((double)skey[mid - 1] >= thr) hi = mid; else lo = mid + 1;
+            }
+            ktab[seg * (size_t)(kTabN + 1) + t] = lo;
+        }
+    }
     if (tid == 0) {
         // invalid values win over a range overflow, which wins over an all-zero layer
         int f = s_flags;
@@ -219,9 +302,9 @@ struct LayerSearch {
     const uint64_t* c;       // c[k-1] = C_k
     int k_lo, k_hi, k;
     int cstep_w;             // N - 1 when the coarse probes exist, else 0
-    uint64_t cval;           // coarse probe of this lane: C at 1 + ((j+1) * (N-1)) / 33
+    double cval;             // coarse probe of this lane: C at 1 + ((j+1) * (N-1)) / 33
     int wbase;               // window: lane j holds C_{wbase + j}; wbase = 0: empty
-    uint64_t wval;
+    double wval;             // (the sums stay below 2^53, so they are exact as doubles)
 };
 
 __device__ __forceinline__ uint32_t ballot32(bool pred, int lane) {
@@ -233,34 +316,38 @@ __device__ __forceinline__ uint32_t ballot32(bool pred, int lane) {
 __device__ __forceinline__ int search_layer(LayerSearch& s, double thr, int N, int lane) {
     const int j = lane & 31;
     int a = s.k_lo, e = s.k_hi;
-    if (s.cstep_w) {
-        const int kc = 1 + ((j + 1) * s.cstep_w) / 33;
-        const bool in = kc >= a && kc < e, ge = (double)s.cval >= thr;
-        const uint32_t m_ge = ballot32(in && ge, lane), m_lt = ballot32(in && !ge, lane);
-        if (m_ge) e = 1 + ((__builtin_ctz(m_ge) + 1) * s.cstep_w) / 33;
-        if (m_lt) a = 2 + ((32 - __builtin_clz(m_lt)) * s.cstep_w) / 33;
-    }
-    while (e - a > kSearchGroup) {
-        const int width = e - a;
-        const int kj = a + ((j + 1) * width) / 33;                  // a < kj < e, ascending in j
-        const bool ge = (double)s.c[kj - 1] >= thr;
-        const uint32_t m_ge = ballot32(ge, lane);
-        if (m_ge == 0) {
-            a = a + (32 * width) / 33 + 1;
-        } else {
-            const int js = __builtin_ctz(m_ge);
-            e = a + ((js + 1) * width) / 33;
-            if (js > 0) a = a + (js * width) / 33 + 1;
+    // once the bracket lies inside the window, an iteration is one compare and one ballot
+    const bool inside = s.wbase != 0 && a >= s.wbase && e <= s.wbase + kSearchGroup;
+    if (!inside) {
+        if (s.cstep_w) {
+            const int kc = 1 + ((j + 1) * s.cstep_w) / 33;
+            const bool in = kc >= a && kc < e, ge = s.cval >= thr;
+            const uint32_t m_ge = ballot32(in && ge, lane), m_lt = ballot32(in && !ge, lane);
+            if (m_ge) e = 1 + ((__builtin_ctz(m_ge) + 1) * s.cstep_w) / 33;
+            if (m_lt) a = 2 + ((32 - __builtin_clz(m_lt)) * s.cstep_w) / 33;
+        }
+        while (e - a > kSearchGroup) {
+            const int width = e - a;
+            const int kj = a + ((j + 1) * width) / 33;              // a < kj < e, ascending in j
+            const bool ge = (double)s.c[kj - 1] >= thr;
+            const uint32_t m_ge = ballot32(ge, lane);
+            if (m_ge == 0) {
+                a = a + (32 * width) / 33 + 1;
+            } else {
+                const int js = __builtin_ctz(m_ge);
+                e = a + ((js + 1) * width) / 33;
+                if (js > 0) a = a + (js * width) / 33 + 1;
+            }
+        }
+        if (a < e && (s.wbase == 0 || a < s.wbase || e > s.wbase + kSearchGroup)) {
+            // anchor the window at the bracket when it already fits: every later search stays inside it
+            s.wbase = s.k_hi - s.k_lo <= kSearchGroup ? s.k_lo : a;
+            s.wval = s.wbase + j <= N ? (double)s.c[s.wbase + j - 1] : INFINITY;
         }
     }
     if (a < e) {
-        if (s.wbase == 0 || a < s.wbase || e > s.wbase + kSearchGroup) {
-            // anchor the window at the bracket when it already fits: every later search stays inside it
-            s.wbase = s.k_hi - s.k_lo <= kSearchGroup ? s.k_lo : a;
-            s.wval = s.wbase + j <= N ? s.c[s.wbase + j - 1] : ~0ull;
-        }
         const int kk = s.wbase + j;
-        const uint32_t m = ballot32(kk >= a && kk < e && (double)s.wval >= thr, lane);
+        const uint32_t m = ballot32(kk >= a && kk < e && s.wval >= thr, lane);
         if (m) e = s.wbase + __builtin_ctz(m);
     }
     return e;
@@ -268,7 +355,7 @@ __device__ __forceinline__ int search_layer(LayerSearch& s, double thr, int N, i
 
 __global__ void __launch_bounds__(kSearchThreads)
 search_kernel(int L, int N, const uint64_t* __restrict__ cum, const int32_t* __restrict__ seg_status,
-              int64_t budget, int64_t tol, int max_iters, int fixup, int32_t* __restrict__ lengths,
+              const int32_t* __restrict__ ktab, int64_t budget, int64_t tol, int max_iters, int fixup, int32_t* __restrict__ lengths,
               double* __restrict__ p_out, int32_t* __restrict__ iters_out,
               int64_t* __restrict__ raw_total_out, int32_t* __restrict__ status) {
     __shared__ int s_sorted[kMaxL];
@@ -276,12 +363,32 @@ search_kernel(int L, int N, const uint64_t* __restrict__ cum, const int32_t* __r
     __shared__ int s_k[2][kMaxL];
     __shared__ int s_sum[3];     // total length of iteration it in s_sum[it % 3]
     __shared__ int s_st;
+    __shared__ int s_ktot[kTabN + 1];
+    extern __shared__ int s_tab[];                        // with a table: the sequence's L rows of kTabN + 1 ints
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1);
     const int grp = tid / kSearchGroup, ngrp = blockDim.x / kSearchGroup;
-
+    const bool tab = ktab != nullptr;
+    // the table of the sequence into LDS (read before the status is known: the row of a refused layer holds
+    // some in-range integers, and is not used)
+    if (tab) {
+        const int4* src = (const int4*)(ktab + (size_t)b * L * (kTabN + 1));
+        for (int i = tid; i < L * (kTabN + 1) / 4; i += blockDim.x) ((int4*)s_tab)[i] = src[i];
+    }
     if (tid == 0) { s_st = 0; s_sum[0] = 0; s_sum[1] = 0; s_sum[2] = 0; }
+    for (int t = tid; t <= kTabN; t += blockDim.x) s_ktot[t] = 0;
     __syncthreads();
     if (tid < L && seg_status[(size_t)b * L + tid]) atomicOr(&s_st, seg_status[(size_t)b * L + tid]);
+    if (tab) {
+        // total length of the sequence at every tabulated ratio: a thread adds up to 8 layers of one column
+        const int nchunk = (L + 7) / 8;
+        for (int i = tid; i < nchunk * (kTabN + 1); i += blockDim.x) {
+            const int t = i & kTabN, l0 = (i >> kTabBits) * 8;
+            int sum = 0;
+#pragma unroll
+            for (int l = 0; l < 8; ++l) sum += l0 + l < L ? s_tab[(l0 + l) * (kTabN + 1) + t] : 0;
+            atomicAdd(&s_ktot[t], sum);
+        }
+    }
     __syncthreads();
     const int st = s_st;
     if (st) {
@@ -307,18 +414,52 @@ search_kernel(int L, int N, const uint64_t* __restrict__ cum, const int32_t* __r
         const int l = grp + i * ngrp;
         const bool act = l < L;
         ls[i].c = cum + ((size_t)b * L + (act ? l : 0)) * (size_t)N;
-        ls[i].k_lo = 1; ls[i].k_hi = N; ls[i].k = 1; ls[i].wbase = 0; ls[i].wval = 0;
+        ls[i].k_lo = 1; ls[i].k_hi = N; ls[i].k = 1; ls[i].wbase = 0; ls[i].wval = 0.0;
         ls[i].cstep_w = N - 1 > kSearchGroup ? N - 1 : 0;
-        ls[i].cval = 0;
+        ls[i].cval = 0.0;
         T[i] = 0.0;
         if (act) {
             T[i] = (double)ls[i].c[N - 1];
-            if (ls[i].cstep_w) ls[i].cval = ls[i].c[((lane & 31) + 1) * ls[i].cstep_w / 33];   // C at 1 + that
+            if (ls[i].cstep_w) ls[i].cval = (double)ls[i].c[((lane & 31) + 1) * ls[i].cstep_w / 33];   // C at 1 + that
         }
     }
     double p1 = 0.0, p2 = 1.0, p = 0.5;
-    int iters = 0, K = 0;
-    for (int it = 1; it <= max_iters; ++it) {
+    int iters = 0, K = 0, it0 = 1;
+    if (tab) {
+        // the tabulated steps: every thread walks them alike (s_ktot is complete since the status barrier)
+        int t_lo = -1, t_hi = kTabN, t_last = -1;         // table columns of p1, p2 (none for 0 and 1) and p
+        bool stop = false;
+        for (; it0 <= max_iters && it0 <= kTabBits; ++it0) {
+            p = 0.5 * (p1 + p2);                          // a multiple of 2^-it0: never equal to p1 or p2
+            t_last = (int)(p * (double)(kTabN + 1)) - 1;
+            K = s_ktot[t_last];
+            iters = it0;
+            const int64_t delta = (int64_t)K - budget;
+            if ((delta < 0 ? -delta : delta) <= tol) { stop = true; break; }
+            if (delta < 0) { p1 = p; t_lo = t_last; } else { p2 = p; t_hi = t_last; }
+        }
+        if (stop || it0 > max_iters) {                    // ended inside the table
+            if (tid == 0) { p_out[b] = p; iters_out[b] = iters; raw_total_out[b] = K; status[b] = 0; }
+            const int k_mine = tid < L ? s_tab[tid * (kTabN + 1) + t_last] : 0;
+            if (!fixup || K == budget) {
+                if (tid < L) lengths[(size_t)b * L + tid] = k_mine;
+                return;
+            }
+            if (tid < kWave)
+                rescale_wave(L, N, tid < L ? (uint64_t)k_mine : 0, (uint64_t)K, budget, lengths + (size_t)b * L, s_sorted, s_len);
+            return;
+        }
+        // the brackets the earlier steps would have left: the lengths at p1 and p2
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int l = grp + i * ngrp;
+            if (l < L) {
+                if (t_lo >= 0) ls[i].k_lo = s_tab[l * (kTabN + 1) + t_lo];
+                if (t_hi < kTabN) ls[i].k_hi = s_tab[l * (kTabN + 1) + t_hi];
+            }
+        }
+    }
+    for (int it = it0; it <= max_iters; ++it) {
         const double mid = 0.5 * (p1 + p2);
         if (mid == p1 || mid == p2) break;
         p = mid;
@@ -428,30 +569,57 @@ gini_kernel(int N, const uint64_t* __restrict__ cum, double* __restrict__ gini) 
 
 static int pow2_at_least(int n) { int p = 64; while (p < n) p <<= 1; return p; }
 
-size_t select_ws_bytes(int B, int L, int N) { (void)N; return (size_t)B * L * sizeof(int32_t); }
-
-hipError_t launch_select(int B, int L, int N, const float* importance, const pkv_select_params& pr,
-                         int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
-                         int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, hipStream_t st) {
-    int32_t* seg_status = (int32_t*)ws;
-    const int P = pow2_at_least(N);
-    int nt = P / 2;
-    if (nt < 64) nt = 64;
-    if (nt > 1024) nt = 1024;
+// one workgroup per segment; keys per thread: 1 for up to 64 keys, 2 up to 2048, then 4 and 8 (1024 threads).
+// (Fewer, fatter wavefronts -- four with P / 256 keys per lane -- were slower: 9.2 us against 7.7 us for the
+// sort at N = 680; a stage is bound by the latency of its shuffle, which more wavefronts hide.)
+template <int E>
+static hipError_t launch_sort_prefix_e(int nseg, int N, int P, const float* importance, int32_t* order,
+                                       uint64_t* cum, float* prefix, int32_t* seg_status, int32_t* ktab,
+                                       hipStream_t st) {
     const size_t lds = (size_t)P * sizeof(uint64_t);
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)sort_prefix_kernel,
+        hipError_t e = hipFuncSetAttribute((const void*)sort_prefix_kernel<E>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(sort_prefix_kernel, dim3(B * L), dim3(nt), lds, st, N, P, importance, order, cum,
-                       prefix, seg_status);
-    hipError_t e = hipGetLastError();
+    hipLaunchKernelGGL(sort_prefix_kernel<E>, dim3(nseg), dim3(P / E), lds, st, N, P, importance, order, cum,
+                       prefix, seg_status, ktab);
+    return hipGetLastError();
+}
+static hipError_t launch_sort_prefix(int nseg, int N, const float* importance, int32_t* order, uint64_t* cum,
+                                     float* prefix, int32_t* seg_status, int32_t* ktab, hipStream_t st) {
+    const int P = pow2_at_least(N);
+    if (P <= 64) return launch_sort_prefix_e<1>(nseg, N, P, importance, order, cum, prefix, seg_status, ktab, st);
+    if (P <= 2048) return launch_sort_prefix_e<2>(nseg, N, P, importance, order, cum, prefix, seg_status, ktab, st);
+    if (P <= 4096) return launch_sort_prefix_e<4>(nseg, N, P, importance, order, cum, prefix, seg_status, ktab, st);
+    if (P <= 8192) return launch_sort_prefix_e<8>(nseg, N, P, importance, order, cum, prefix, seg_status, ktab, st);
+    return hipErrorInvalidValue;
+}
+
+// a status word per segment, then (256-byte aligned) a table row per segment
+static size_t select_tab_offset(int B, int L) { return ((size_t)B * L * sizeof(int32_t) + 255) / 256 * 256; }
+size_t select_ws_bytes(int B, int L, int N) {
+    (void)N;
+    return select_tab_offset(B, L) + (size_t)B * L * (kTabN + 1) * sizeof(int32_t);
+}
+
+hipError_t launch_select(int B, int L, int N, const float* importance, const pkv_select_params& pr,
+                         int32_t* order, uint64_t* cum, float* prefix, int32_t* lengths, double* p_out,
+                         int32_t* iters, int64_t* raw_total, int32_t* status, void* ws, bool with_table,
+                         hipStream_t st) {
+    int32_t* seg_status = (int32_t*)ws;
+    int32_t* ktab = with_table ? (int32_t*)((unsigned char*)ws + select_tab_offset(B, L)) : nullptr;
+    hipError_t e = launch_sort_prefix(B * L, N, importance, order, cum, prefix, seg_status, ktab, st);
     if (e != hipSuccess) return e;
     // one 32-lane group per layer (two layers per group beyond 32), whole wavefronts
     int search_threads = (L * kSearchGroup + kWave - 1) / kWave * kWave;
     if (search_threads > kSearchThreads) search_threads = kSearchThreads;
-    hipLaunchKernelGGL(search_kernel, dim3(B), dim3(search_threads), 0, st, L, N, cum, seg_status,
+    const size_t tab_lds = ktab ? (size_t)L * (kTabN + 1) * sizeof(int32_t) : 0;
+    if (tab_lds > 32 * 1024) {
+        e = hipFuncSetAttribute((const void*)search_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)tab_lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(search_kernel, dim3(B), dim3(search_threads), tab_lds, st, L, N, cum, seg_status, ktab,
                        (int64_t)pr.budget_tokens, (int64_t)pr.tol_tokens, (int)pr.max_iters, (int)pr.fixup,
                        lengths, p_out, iters, raw_total, status);
     return hipGetLastError();
@@ -492,26 +660,15 @@ hipError_t launch_select_static(int B, int L, int N, const float* importance, co
         }
         ptr = g_scratch_ptr[dev];
     }
+    // no table here: a status word is all a segment needs, the search walks every step on the rows
     return launch_select(B, L, N, importance, pr, order, cum, prefix, lengths, p_out, iters, raw_total, status,
-                         ptr, st);
+                         ptr, false, st);
 }
 
 hipError_t launch_rank(int B, int L, int N, const float* importance, int32_t* order, uint64_t* cum,
                        float* prefix, int32_t* status, void* ws, hipStream_t st) {
     int32_t* seg_status = (int32_t*)ws;
-    const int P = pow2_at_least(N);
-    int nt = P / 2;
-    if (nt < 64) nt = 64;
-    if (nt > 1024) nt = 1024;
-    const size_t lds = (size_t)P * sizeof(uint64_t);
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void*)sort_prefix_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(sort_prefix_kernel, dim3(B * L), dim3(nt), lds, st, N, P, importance, order, cum,
-                       prefix, seg_status);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_sort_prefix(B * L, N, importance, order, cum, prefix, seg_status, nullptr, st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(status_reduce_kernel, dim3(B), dim3(kWave), 0, st, L, seg_status, status);
     return hipGetLastError();

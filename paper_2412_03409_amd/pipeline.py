@@ -38,7 +38,7 @@ class HotPath:
             iters=torch.empty(Bn, dtype=torch.int32, device=dev),
             raw_total=torch.empty(Bn, dtype=torch.int64, device=dev),
             status=torch.empty(Bn, dtype=torch.int32, device=dev))
-        self.sel_ws = torch.empty(max(256, Bn * L * 4), dtype=torch.uint8, device=dev)
+        self.sel_ws = torch.empty(max(256, B_.select_workspace_bytes(Bn, L, N)), dtype=torch.uint8, device=dev)
         budget_cap = min(self.budget_tokens, L * N)
         self.cache_tokens = B_.prefixkv_cache_tokens_upper_bound(Bn, budget_cap, L, self.decode_capacity)
         self.cache = B_.CompactResult(

@@ -39,7 +39,10 @@ def test_workspace_queries():
     f32 = (1 * 4 * 2 * 128 * 4 + 255) // 256 * 256
     assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 4, 2, 2, 128, 64, P.PKV_F32) == 2 * f32
     assert P.prefixkv_workspace_bytes(Bd.OP_IMPORTANCE, 1, 4, 2, 2, 128, 64, P.PKV_F32, has_lse=True) == f32
-    assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 32, 32, 32, 680, 128, dt) == 2 * 32 * 4
+    # a status word per (sequence, layer), padded to 256 bytes, then 256 ints of tabulated lengths per layer
+    assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 32, 32, 32, 680, 128, dt) == 256 + 2 * 32 * 1024
+    assert P.select_workspace_bytes(2, 32, 680) == 256 + 2 * 32 * 1024
+    assert P.select_workspace_bytes(1, 5, 9) == 256 + 5 * 1024
     assert P.prefixkv_workspace_bytes(Bd.OP_DECODE, 1, 32, 32, 32, 680, 128, dt) == 0
     # invalid shapes give 0
     assert P.prefixkv_workspace_bytes(Bd.OP_SELECT, 2, 65, 32, 32, 680, 128, dt) == 0
