@@ -40,15 +40,47 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int m) {
-    uint32_t lo = __shfl_xor((uint32_t)v, m, kWave);
-    uint32_t hi = __shfl_xor((uint32_t)(v >> 32), m, kWave);
+// Value of lane (l ^ J) for J = 1 .. 32 without a trip through the LDS crossbar: quad permutes (1, 2), row
+// rotations (4, 8: a rotation by half a row of 16 is the exchange itself, by a quarter it is the exchange for
+// one half of the lanes each way) and the 16- and 32-lane swaps of gfx950.
+template <int J>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t x, int lane) {
+    if constexpr (J == 1) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    else if constexpr (J == 2) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    else if constexpr (J == 4) {
+        const uint32_t dn = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x124, 0xF, 0xF, true);   // row_ror:4, from lane - 4
+        const uint32_t up = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x12C, 0xF, 0xF, true);   // row_ror:12, from lane + 4
+        return (lane & 4) ? dn : up;
+    } else if constexpr (J == 8) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xF, 0xF, true);   // row_ror:8
+    else if constexpr (J == 16) {
+        const auto sw = __builtin_amdgcn_permlane16_swap(x, x, false, false);   // [r0 r0 r2 r2], [r1 r1 r3 r3]
+        return (lane & 16) ? sw[0] : sw[1];
+    } else {
+        static_assert(J == 32, "lane distance");
+        const auto sw = __builtin_amdgcn_permlane32_swap(x, x, false, false);   // [lo lo], [hi hi]
+        return (lane & 32) ? sw[0] : sw[1];
+    }
+}
+template <int J>
+__device__ __forceinline__ uint64_t lane_xor_u64(uint64_t v, int lane) {
+    const uint32_t lo = lane_xor<J>((uint32_t)v, lane), hi = lane_xor<J>((uint32_t)(v >> 32), lane);
     return ((uint64_t)hi << 32) | lo;
 }
 
 // The stages of bitonic merge step k whose partner distance is below 64*E, on keys held in registers: a
 // wavefront owns an aligned block of 64*E keys, register e of lane l is position base + 64*e + l.  Distances
 // of 64 and more pair two registers of one lane, smaller ones pair two lanes (one shuffle per key).
+template <int E, int J>
+__device__ __forceinline__ void lane_stage(uint64_t (&r)[E], int k, int base, int lane) {
+    if (J >= k) return;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        const uint64_t a = r[e], b = lane_xor_u64<J>(a, lane);
+        const bool up = ((base + 64 * e + lane) & k) == 0;
+        const bool keep_min = ((lane & J) == 0) == up;
+        r[e] = (a < b) == keep_min ? a : b;
+    }
+}
 template <int E>
 __device__ __forceinline__ void wave_stages(uint64_t (&r)[E], int k, int base, int lane) {
 #pragma unroll
@@ -64,17 +96,12 @@ __device__ __forceinline__ void wave_stages(uint64_t (&r)[E], int k, int base, i
             r[e | je] = sw ? a : b;
         }
     }
-#pragma unroll
-    for (int j = 32; j >= 1; j >>= 1) {                 // between lanes
-        if (j >= k) continue;
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const uint64_t a = r[e], b = shfl_xor_u64(a, j);
-            const bool up = ((base + 64 * e + lane) & k) == 0;
-            const bool keep_min = ((lane & j) == 0) == up;
-            r[e] = (a < b) == keep_min ? a : b;
-        }
-    }
+    lane_stage<E, 32>(r, k, base, lane);                // between lanes
+    lane_stage<E, 16>(r, k, base, lane);
+    lane_stage<E, 8>(r, k, base, lane);
+    lane_stage<E, 4>(r, k, base, lane);
+    lane_stage<E, 2>(r, k, base, lane);
+    lane_stage<E, 1>(r, k, base, lane);
 }
 
 // Ratios served from a table: p = (t + 1) / 2^kTabBits, t = 0 .. kTabN - 1 (rows of kTabN + 1 ints)
@@ -364,29 +391,57 @@ search_kernel(int L, int N, const uint64_t* __restrict__ cum, const int32_t* __r
     __shared__ int s_sum[3];     // total length of iteration it in s_sum[it % 3]
     __shared__ int s_st;
     __shared__ int s_ktot[kTabN + 1];
+    __shared__ unsigned long long s_below[(kTabN + 1) / 64], s_hit[(kTabN + 1) / 64];
     extern __shared__ int s_tab[];                        // with a table: the sequence's L rows of kTabN + 1 ints
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1);
     const int grp = tid / kSearchGroup, ngrp = blockDim.x / kSearchGroup;
     const bool tab = ktab != nullptr;
+    // The layers of this group: grp and grp + ngrp (ngrp >= min(L, 32), L <= 64).  Their totals and coarse
+    // probes are requested here, together with the table and ahead of the status, so that the kernel starts
+    // with one round trip to memory instead of three (the rows of a refused layer hold unspecified but
+    // readable values).
+    LayerSearch ls[2];
+    double T[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int l = grp + i * ngrp;
+        const bool act = l < L;
+        ls[i].c = cum + ((size_t)b * L + (act ? l : 0)) * (size_t)N;
+        ls[i].k_lo = 1; ls[i].k_hi = N; ls[i].k = 1; ls[i].wbase = 0; ls[i].wval = 0.0;
+        ls[i].cstep_w = N - 1 > kSearchGroup ? N - 1 : 0;
+        ls[i].cval = 0.0;
+        T[i] = 0.0;
+        if (act) {
+            T[i] = (double)ls[i].c[N - 1];
+            if (ls[i].cstep_w) ls[i].cval = (double)ls[i].c[((lane & 31) + 1) * ls[i].cstep_w / 33];   // C at 1 + that
+        }
+    }
     // the table of the sequence into LDS (read before the status is known: the row of a refused layer holds
     // some in-range integers, and is not used)
     if (tab) {
         const int4* src = (const int4*)(ktab + (size_t)b * L * (kTabN + 1));
         for (int i = tid; i < L * (kTabN + 1) / 4; i += blockDim.x) ((int4*)s_tab)[i] = src[i];
     }
+    const int st_mine = tid < L ? seg_status[(size_t)b * L + tid] : 0;
     if (tid == 0) { s_st = 0; s_sum[0] = 0; s_sum[1] = 0; s_sum[2] = 0; }
-    for (int t = tid; t <= kTabN; t += blockDim.x) s_ktot[t] = 0;
     __syncthreads();
-    if (tid < L && seg_status[(size_t)b * L + tid]) atomicOr(&s_st, seg_status[(size_t)b * L + tid]);
+    if (st_mine) atomicOr(&s_st, st_mine);
     if (tab) {
-        // total length of the sequence at every tabulated ratio: a thread adds up to 8 layers of one column
-        const int nchunk = (L + 7) / 8;
-        for (int i = tid; i < nchunk * (kTabN + 1); i += blockDim.x) {
-            const int t = i & kTabN, l0 = (i >> kTabBits) * 8;
+        // Total length of the sequence at every tabulated ratio, and how it compares with the budget: one bit
+        // per ratio for "below the budget by more than the tolerance" and one for "within the tolerance".
+        // The tabulated steps of the search then only test bits.
+        for (int t0 = 0; t0 <= kTabN; t0 += blockDim.x) {         // whole wavefronts: a wavefront = one mask word
+            const int t = t0 + tid;
             int sum = 0;
-#pragma unroll
-            for (int l = 0; l < 8; ++l) sum += l0 + l < L ? s_tab[(l0 + l) * (kTabN + 1) + t] : 0;
-            atomicAdd(&s_ktot[t], sum);
+            if (t < kTabN)
+                for (int l = 0; l < L; ++l) sum += s_tab[l * (kTabN + 1) + t];
+            const int64_t d = (int64_t)sum - budget;
+            const unsigned long long mb = __builtin_amdgcn_ballot_w64(t < kTabN && d < -tol);
+            const unsigned long long mh = __builtin_amdgcn_ballot_w64(t < kTabN && (d < 0 ? -d : d) <= tol);
+            if (t <= kTabN) {
+                s_ktot[t] = sum;
+                if (lane == 0) { s_below[t >> 6] = mb; s_hit[t >> 6] = mh; }
+            }
         }
     }
     __syncthreads();
@@ -406,38 +461,32 @@ search_kernel(int L, int N, const uint64_t* __restrict__ cum, const int32_t* __r
         return;
     }
 
-    // the layers of this group: grp and grp + ngrp (ngrp >= min(L, 32), L <= 64)
-    LayerSearch ls[2];
-    double T[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int l = grp + i * ngrp;
-        const bool act = l < L;
-        ls[i].c = cum + ((size_t)b * L + (act ? l : 0)) * (size_t)N;
-        ls[i].k_lo = 1; ls[i].k_hi = N; ls[i].k = 1; ls[i].wbase = 0; ls[i].wval = 0.0;
-        ls[i].cstep_w = N - 1 > kSearchGroup ? N - 1 : 0;
-        ls[i].cval = 0.0;
-        T[i] = 0.0;
-        if (act) {
-            T[i] = (double)ls[i].c[N - 1];
-            if (ls[i].cstep_w) ls[i].cval = (double)ls[i].c[((lane & 31) + 1) * ls[i].cstep_w / 33];   // C at 1 + that
-        }
-    }
     double p1 = 0.0, p2 = 1.0, p = 0.5;
     int iters = 0, K = 0, it0 = 1;
     if (tab) {
         // the tabulated steps: every thread walks them alike (s_ktot is complete since the status barrier)
         int t_lo = -1, t_hi = kTabN, t_last = -1;         // table columns of p1, p2 (none for 0 and 1) and p
         bool stop = false;
+        unsigned long long below[(kTabN + 1) / 64], hit[(kTabN + 1) / 64];
+#pragma unroll
+        for (int w = 0; w < (kTabN + 1) / 64; ++w) { below[w] = s_below[w]; hit[w] = s_hit[w]; }
         for (; it0 <= max_iters && it0 <= kTabBits; ++it0) {
-            p = 0.5 * (p1 + p2);                          // a multiple of 2^-it0: never equal to p1 or p2
-            t_last = (int)(p * (double)(kTabN + 1)) - 1;
-            K = s_ktot[t_last];
+            // p = (p1 + p2) / 2 is a multiple of 2^-it0, never equal to p1 or p2; its column is the middle of
+            // the columns of p1 and p2
+            t_last = (t_lo + t_hi) >> 1;
             iters = it0;
-            const int64_t delta = (int64_t)K - budget;
-            if ((delta < 0 ? -delta : delta) <= tol) { stop = true; break; }
-            if (delta < 0) { p1 = p; t_lo = t_last; } else { p2 = p; t_hi = t_last; }
+            unsigned long long wb = below[0], wh = hit[0];
+#pragma unroll
+            for (int w = 1; w < (kTabN + 1) / 64; ++w)
+                if ((t_last >> 6) == w) { wb = below[w]; wh = hit[w]; }
+            if ((wh >> (t_last & 63)) & 1) { stop = true; break; }
+            if ((wb >> (t_last & 63)) & 1) t_lo = t_last; else t_hi = t_last;
         }
+        // the ratios as Algorithm 1 would hold them: exact dyadic numbers
+        p1 = (double)(t_lo + 1) * (1.0 / (double)(kTabN + 1));
+        p2 = (double)(t_hi + 1) * (1.0 / (double)(kTabN + 1));
+        p = (double)(t_last + 1) * (1.0 / (double)(kTabN + 1));
+        K = s_ktot[t_last];
         if (stop || it0 > max_iters) {                    // ended inside the table
             if (tid == 0) { p_out[b] = p; iters_out[b] = iters; raw_total_out[b] = K; status[b] = 0; }
             const int k_mine = tid < L ? s_tab[tid * (kTabN + 1) + t_last] : 0;
