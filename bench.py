@@ -238,12 +238,14 @@ def measure(P, HotPath, w, r, K, W, use_graph, d_ev=None, x=None, dec=None):
         assert int(hp.cache.lens.sum()) + w.B * w.L * min(T, d_ev) == cached_tokens_under_pruning(lens0, w.N, T, d_ev), \
             "decode loop did not run to the end"
     esz = w.elem_bytes
-    flops = 2 * w.B * w.L * w.H * w.N * (w.N + 1) * w.D   # two causal QK^T passes (lse, column sums)
+    # two causal QK^T products per head (the row lse, then the column sums), both inside one kernel that
+    # reads Q and K from HBM once
+    flops = 2 * w.B * w.L * w.H * w.N * (w.N + 1) * w.D
     imp_tflops = flops / (imp_ms * 1e-3) / 1e12
     cmp_bytes = 2 * int(lens0.sum()) * w.Hkv * w.D * esz * 2 + w.B * w.L * w.N * 4
     stages = {
         "importance": {"ms": round(imp_ms, 4), "tflops": round(imp_tflops, 1),
-                       "frac_mfma_bf16": round(imp_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "passes": 2},
+                       "frac_mfma_bf16": round(imp_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "products": 2, "kernels": 1},
         "select": {"ms": round(sel_ms, 4), "iters": hp.sel.iters.tolist()[:4], "p": hp.sel.p.tolist()[:2]},
         "compact": {"ms": round(cmp_ms, 4), "GBps": round(cmp_bytes / (cmp_ms * 1e-3) / 1e9, 1)},
         "decode_loop": {"ms": round(dec_ms, 4), "us_per_decode_step": round(dec_ms * 1e3 / T, 2),
@@ -330,7 +332,7 @@ def time_extras(P, w, x, hp, Bk, T, reps=5):
         t = ms(lambda: P.prefixkv_prefill_attn(x["q"], x["k"], x["v"], x["scale"], out=o, lse=lse))
         out["prefill_attn"] = {"ms": round(t, 4), "tflops": round(2 * flops1 / t / 1e9, 1)}
         t = ms(lambda: P.prefixkv_importance(x["q"], x["k"], x["scale"], lse=lse))
-        out["importance_with_lse"] = {"ms": round(t, 4), "tflops": round(flops1 / t / 1e9, 1), "passes": 1}
+        out["importance_with_lse"] = {"ms": round(t, 4), "tflops": round(flops1 / t / 1e9, 1), "products": 1, "kernels": 1}
         del o
     rk = P.prefixkv_rank(hp.importance)
     out["rank"] = {"ms": round(ms(lambda: P.prefixkv_rank(hp.importance, out=rk)), 4)}

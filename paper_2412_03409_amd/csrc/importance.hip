@@ -332,31 +332,60 @@ importance_fused_kernel(FusedParams p) {
     }
 }
 
-// importance[b,l,n] = (1/H) * sum_h sum_g partial[b,l,h,g,n] over the workgroups g whose rows see key n,
-// added in (h, g) order.
-__global__ void head_mean_fused_kernel(int H, int G, int N, int T, int WV, long long total, const float* __restrict__ partial,
-                                       float* __restrict__ importance) {
-    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total) return;
-    const long long bl = i / N;
-    const int n = (int)(i % N);
+// importance[b,l,n] = (1/H) * sum_h sum_g partial[b,l,h,g,n] over the workgroups g whose rows see key n.
+// A workgroup takes 64 consecutive keys; its four wavefronts each add a quarter of the heads in (h, g) order
+// (several loads in flight: the sum is bound by memory latency, not by bytes) and the four sums are added in
+// wavefront order, so the result does not depend on timing.
+constexpr int kMeanKeys = 64, kMeanParts = 4;
+__global__ void __launch_bounds__(kMeanKeys * kMeanParts)
+head_mean_fused_kernel(int H, int G, int N, int T, int WV, long long total, const float* __restrict__ partial,
+                       float* __restrict__ importance) {
+    __shared__ float s_acc[kMeanParts][kMeanKeys];
+    const int lane = threadIdx.x % kMeanKeys, part = threadIdx.x / kMeanKeys;
+    const long long i = (long long)blockIdx.x * kMeanKeys + lane;
+    const bool live = i < total;
+    const long long bl = live ? i / N : 0;
+    const int n = live ? (int)(i % N) : 0;
     // workgroup g covers keys below 32*(T - WV*g): g <= (T - 1 - n/32) / WV
     const int gmax = min(G - 1, (T - 1 - n / 32) / WV);
+    const int per = (H + kMeanParts - 1) / kMeanParts;
+    const int h0 = part * per, h1 = min(H, h0 + per);
     const float* src = partial + (size_t)bl * H * G * N + n;
     float acc = 0.f;
-    for (int h = 0; h < H; ++h) {
-        const float* sh = src + (size_t)h * G * N;
-        int g = 0;
-        for (; g + 4 <= gmax + 1; g += 4) {
-            float v[4];
+    if (live) {
+        if (G == 1) {
+            int h = h0;
+            for (; h + 8 <= h1; h += 8) {
+                float v[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = sh[(size_t)(g + j) * N];
+                for (int j = 0; j < 8; ++j) v[j] = src[(size_t)(h + j) * N];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc += v[j];
+                for (int j = 0; j < 8; ++j) acc += v[j];
+            }
+            for (; h < h1; ++h) acc += src[(size_t)h * N];
+        } else {
+            for (int h = h0; h < h1; ++h) {
+                const float* sh = src + (size_t)h * G * N;
+                int g = 0;
+                for (; g + 4 <= gmax + 1; g += 4) {
+                    float v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = sh[(size_t)(g + j) * N];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc += v[j];
+                }
+                for (; g <= gmax; ++g) acc += sh[(size_t)g * N];
+            }
         }
-        for (; g <= gmax; ++g) acc += sh[(size_t)g * N];
     }
-    importance[i] = acc / (float)H;
+    s_acc[part][lane] = acc;
+    __syncthreads();
+    if (part == 0 && live) {
+        float sum = s_acc[0][lane];
+#pragma unroll
+        for (int q = 1; q < kMeanParts; ++q) sum += s_acc[q][lane];
+        importance[i] = sum / (float)H;
+    }
 }
 
 // importance[b,l,n] = (1/H) * sum_h partial[b,l,h,n], heads added in order.
@@ -496,8 +525,8 @@ hipError_t launch_importance(const pkv_shape& s, const void* q, Strides qs, cons
         else hipLaunchKernelGGL((importance_fused_kernel<64, false, kFusedWaves, kFusedOcc>), grid, block, 0, st, p);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL(head_mean_fused_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, s.H, p.G, s.N,
-                       p.T, kFusedWaves, total, partial, importance);
+    hipLaunchKernelGGL(head_mean_fused_kernel, dim3((unsigned)((total + kMeanKeys - 1) / kMeanKeys)),
+                       dim3(kMeanKeys * kMeanParts), 0, st, s.H, p.G, s.N, p.T, kFusedWaves, total, partial, importance);
     return hipGetLastError();
 }
 

@@ -16,7 +16,8 @@ from pkv_workloads import CONFIGS, make_decode, make_prefill
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-IMP_RTOL, OUT_ATOL = 1e-3, 2e-2
+from tolerances import (DECODE_ATOL as OUT_ATOL, IMPORTANCE_RTOL as IMP_RTOL, LSE_ATOL, LSE_RTOL, MERGE_ATOL,
+                        MERGE_RTOL_BF16)
 
 
 def f32(t):
@@ -236,7 +237,7 @@ def test_prefill_attention_feeds_one_pass_importance_at_full_size(name, layers):
             want_out, want_lse = oracle.prefill_attn(f32(x["q"][:1, sl]), f32(x["k"][:1, sl]), f32(x["v"][:1, sl]),
                                                      scale[sl], out_bf16=True)
             assert np.abs(f32(out[:1, sl]) - want_out).max() <= OUT_ATOL
-            np.testing.assert_allclose(lse[:1, sl].cpu().numpy(), want_lse, rtol=1e-4, atol=3e-4)
+            np.testing.assert_allclose(lse[:1, sl].cpu().numpy(), want_lse, rtol=LSE_RTOL, atol=LSE_ATOL)
         else:
             m_lo = w.N - 96
             want = oracle.importance(f32(x["q"][:1, sl]), f32(x["k"][:1, sl]), scale[sl], m_lo=m_lo)
@@ -281,9 +282,9 @@ def test_merging_at_full_size(name, layers):
             assert (oracle.match_cosine(want, src, g) >= best - 5e-6).all()
             assert (g != wm).mean() < 1e-3
             oracle.merge_by_match(want, nm, src, g, storage_bf16=True)
-            np.testing.assert_allclose(seg(got), oracle.segment(want, nm, 0, 0)[:, :n], rtol=2.0 ** -7, atol=1e-4)
+            np.testing.assert_allclose(seg(got), oracle.segment(want, nm, 0, 0)[:, :n], rtol=MERGE_RTOL_BF16, atol=MERGE_ATOL)
         # positional merging
         want = oracle.compact(k1, v1, sel_order[:, sl], sel_len[:, sl], 2)
         oracle.merge_position(want, k1, v1, storage_bf16=True)
-        np.testing.assert_allclose(seg(hp.cache.kc), oracle.segment(want, "kc", 0, 0)[:, :n], rtol=2.0 ** -7, atol=1e-4)
-        np.testing.assert_allclose(seg(hp.cache.vc), oracle.segment(want, "vc", 0, 0)[:, :n], rtol=2.0 ** -7, atol=1e-4)
+        np.testing.assert_allclose(seg(hp.cache.kc), oracle.segment(want, "kc", 0, 0)[:, :n], rtol=MERGE_RTOL_BF16, atol=MERGE_ATOL)
+        np.testing.assert_allclose(seg(hp.cache.vc), oracle.segment(want, "vc", 0, 0)[:, :n], rtol=MERGE_RTOL_BF16, atol=MERGE_ATOL)

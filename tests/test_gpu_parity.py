@@ -12,8 +12,8 @@ from pkv_workloads import CONFIGS, make_decode, make_prefill, synthetic_importan
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-IMP_RTOL = 1e-3     # importance: relative, bf16 inputs, fp32 accumulation
-OUT_ATOL = 2e-2     # decode attention output: absolute
+from tolerances import (DECODE_ATOL as OUT_ATOL, IMPORTANCE_RTOL as IMP_RTOL, LSE_ATOL, LSE_RTOL, MERGE_ATOL,
+                        MERGE_RTOL_BF16, MERGE_RTOL_F32)
 
 
 def np32(t):
@@ -94,7 +94,7 @@ def test_importance_and_prefill_random_shapes():
             want_out, want_lse = oracle.prefill_attn(np32(q), np32(k), np32(v), scale.numpy(), out_bf16=True)
             torch.cuda.synchronize()
             assert np.abs(np32(out) - want_out).max() <= OUT_ATOL, case
-            np.testing.assert_allclose(lse_g.cpu().numpy(), want_lse, rtol=1e-4, atol=3e-4)
+            np.testing.assert_allclose(lse_g.cpu().numpy(), want_lse, rtol=LSE_RTOL, atol=LSE_ATOL)
 
 
 def test_importance_strided_inputs_and_determinism():
@@ -376,8 +376,8 @@ def test_merge_feature_matches_oracle(B, L, Hkv, N, D, frac):
             gv = vc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
             # fp32 sums on the GPU, fp64 in the oracle: equal up to one unit in the last place of bf16
             # (and up to the rounding of an fp32 sum where the terms cancel)
-            np.testing.assert_allclose(gk, oracle.segment(want, "kc", b, l)[:, :n], rtol=2.0 ** -7, atol=1e-4)
-            np.testing.assert_allclose(gv, oracle.segment(want, "vc", b, l)[:, :n], rtol=2.0 ** -7, atol=1e-4)
+            np.testing.assert_allclose(gk, oracle.segment(want, "kc", b, l)[:, :n], rtol=MERGE_RTOL_BF16, atol=MERGE_ATOL)
+            np.testing.assert_allclose(gv, oracle.segment(want, "vc", b, l)[:, :n], rtol=MERGE_RTOL_BF16, atol=MERGE_ATOL)
     if frac == 1.0:
         assert (gm == -1).all()
 
@@ -420,7 +420,7 @@ def test_compact_and_merge_random_shapes():
         got, want = run_compact(k, v, sel, cap, budget)
         check_cache(got, want, dtype)
         bf = dtype == torch.bfloat16
-        rtol = 2.0 ** -7 if bf else 2e-6
+        rtol = MERGE_RTOL_BF16 if bf else MERGE_RTOL_F32
 
         def compare():
             torch.cuda.synchronize()
@@ -430,8 +430,8 @@ def test_compact_and_merge_random_shapes():
                     off, cp, n = int(want["seg_off"][b, l]), int(want["caps"][b, l]), int(want["lens"][b, l])
                     gk = kc[off * Hkv * D:(off + cp) * Hkv * D].reshape(Hkv, cp, D)[:, :n]
                     gv = vc[off * Hkv * D:(off + cp) * Hkv * D].reshape(Hkv, cp, D)[:, :n]
-                    np.testing.assert_allclose(gk, oracle.segment(want, "kc", b, l)[:, :n], rtol=rtol, atol=1e-4)
-                    np.testing.assert_allclose(gv, oracle.segment(want, "vc", b, l)[:, :n], rtol=rtol, atol=1e-4)
+                    np.testing.assert_allclose(gk, oracle.segment(want, "kc", b, l)[:, :n], rtol=rtol, atol=MERGE_ATOL)
+                    np.testing.assert_allclose(gv, oracle.segment(want, "vc", b, l)[:, :n], rtol=rtol, atol=MERGE_ATOL)
 
         if case % 2 == 0 or not bf:
             P.prefixkv_merge_position(got, k.to(DEV), v.to(DEV))
@@ -498,14 +498,14 @@ def test_merge_position_matches_oracle(B, L, Hkv, N, D, dtype, frac):
     np.testing.assert_array_equal(got.lens.cpu().numpy(), want["lens"])
     kc, vc = np32(got.kc), np32(got.vc)
     # fp32 sums on the GPU, fp64 in the oracle: equal up to one unit in the last place of the storage dtype
-    rtol = 2.0 ** -7 if bf else 2e-6
+    rtol = MERGE_RTOL_BF16 if bf else MERGE_RTOL_F32
     for b in range(B):
         for l in range(L):
             off, cap, n = int(want["seg_off"][b, l]), int(want["caps"][b, l]), int(want["lens"][b, l])
             gk = kc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
             gv = vc[off * Hkv * D:(off + cap) * Hkv * D].reshape(Hkv, cap, D)[:, :n]
-            np.testing.assert_allclose(gk, oracle.segment(want, "kc", b, l)[:, :n], rtol=rtol, atol=1e-6)
-            np.testing.assert_allclose(gv, oracle.segment(want, "vc", b, l)[:, :n], rtol=rtol, atol=1e-6)
+            np.testing.assert_allclose(gk, oracle.segment(want, "kc", b, l)[:, :n], rtol=rtol, atol=MERGE_ATOL)
+            np.testing.assert_allclose(gv, oracle.segment(want, "vc", b, l)[:, :n], rtol=rtol, atol=MERGE_ATOL)
     if frac == 1.0:   # every group is one position: bit-identical to the plain gather
         plain, pw = run_compact(k, v, sel, 3, budget)
         check_cache(got, pw, dtype)
@@ -805,7 +805,7 @@ def test_prefill_attention_matches_oracle_and_feeds_importance(B, L, H, Hkv, N, 
     torch.cuda.synchronize()
     assert np.isfinite(np32(out)).all()
     assert np.abs(np32(out) - want_out).max() <= OUT_ATOL
-    np.testing.assert_allclose(lse.cpu().numpy(), want_lse, rtol=1e-4, atol=2e-4)
+    np.testing.assert_allclose(lse.cpu().numpy(), want_lse, rtol=LSE_RTOL, atol=LSE_ATOL)
     # the importance stage with this lse (one pass) meets the same bar as with its own (two passes)
     imp1 = P.prefixkv_importance(q.to(DEV), k.to(DEV), scale.to(DEV), lse=lse)
     check_importance(imp1.cpu().numpy(), oracle.importance(np32(q), np32(k), scale.numpy()))
@@ -825,7 +825,7 @@ def test_prefill_attention_negative_scale_and_sinks():
     out, lse = P.prefixkv_prefill_attn(q.to(DEV), k.to(DEV), v.to(DEV), scale.to(DEV))
     want_out, want_lse = oracle.prefill_attn(np32(q), np32(k), np32(v), scale.numpy(), out_bf16=True)
     assert np.abs(np32(out) - want_out).max() <= OUT_ATOL
-    np.testing.assert_allclose(lse.cpu().numpy(), want_lse, rtol=1e-4, atol=2e-4)
+    np.testing.assert_allclose(lse.cpu().numpy(), want_lse, rtol=LSE_RTOL, atol=LSE_ATOL)
 
 
 def test_prefill_attention_strided_inputs_and_refusals():
