@@ -156,6 +156,15 @@ def _median(v):
     return v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
 
 
+def _decode_source_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("decode.hip", "pkv_common.hpp"):
+        with open(os.path.join(ROOT, "paper_2412_03409_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
 def decode_roofline(w, r, lens0, T, dec_ms, d_ev=None):
     """Roofline of the decode launch.  The decode loop is T launches of one kernel (for grouped-query bf16
     caches: a planning kernel and the attention kernel, timed together) and nothing else, back to back on one
@@ -174,8 +183,12 @@ def decode_roofline(w, r, lens0, T, dec_ms, d_ev=None):
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        key = f"decode_attn_kernel/{w.name}/budget{r:g}" + ("" if d_ev is None else f"/evict{d_ev}")
-        traffic = json.load(open(tpath)).get(key)
+        # counter values belong to the kernel source they were measured on: a changed source reports null
+        # until the PMC passes have been run again
+        table = json.load(open(tpath))
+        if table.get("_decode_source_sha256") == _decode_source_digest():
+            key = f"decode_attn_kernel/{w.name}/budget{r:g}" + ("" if d_ev is None else f"/evict{d_ev}")
+            traffic = table.get(key)
     gqa = w.dtype == "bf16" and (w.H // w.Hkv) % 2 == 0
     return {"kernel": "decode_plan_kernel + decode_gqa_kernel" if gqa else "decode_attn_kernel", "bound": "hbm",
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
