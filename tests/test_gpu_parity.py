@@ -137,7 +137,8 @@ def check_select(imp, budget, tol=0, max_iters=64, fixup=True):
 
 @pytest.mark.parametrize("B,L,N", [(1, 1, 1), (1, 3, 5), (2, 4, 128), (3, 32, 680), (2, 40, 680),
                                    (1, 64, 64), (2, 8, 8192), (1, 5, 1025), (2, 7, 2049),
-                                   (1, 2, 33), (2, 3, 34), (1, 33, 100), (1, 6, 1100)])   # probe / window boundaries
+                                   (1, 2, 33), (2, 3, 34), (1, 33, 100), (1, 6, 1100),   # probe / window boundaries
+                                   (1, 64, 680), (1, 2, 4096)])                           # two layers per lane group; 4 keys per lane
 @pytest.mark.parametrize("ties", [False, True])
 def test_select_bit_exact(B, L, N, ties):
     imp = synthetic_importance(B, L, N, seed=B * 1000 + L * 10 + N, ties=ties)
@@ -148,6 +149,7 @@ def test_select_bit_exact(B, L, N, ties):
             check_select(imp, budget)
     check_select(imp, max(L + 1, total // 5), tol=max(1, N // 20))
     check_select(imp, max(L + 1, total // 5), max_iters=7)
+    check_select(imp, max(L + 1, total // 5), max_iters=8)      # the last step the tabulated ratios serve
     check_select(imp, max(L + 1, total // 5), max_iters=9, fixup=False)
     check_select(imp, max(L + 1, total // 2), tol=3, fixup=False)
 
