@@ -129,8 +129,8 @@ typedef struct {
     int32_t fixup;         /* 0 / 1 */
 } pkv_select_params;
 
-/*   ws [dev]: prefixkv_workspace_bytes(PKV_OP_SELECT, shape, 0) bytes; contents on entry and after the
- *   call are unspecified.  It holds one status word per (sequence, layer) and, per layer, the prefix
+/*   ws [dev]: prefixkv_workspace_bytes(PKV_OP_SELECT, shape, 0) bytes, 16-byte aligned (else
+ *   PKV_ERR_WORKSPACE); contents on entry and after the call are unspecified.  It holds one status word per (sequence, layer) and, per layer, the prefix
  *   lengths at the 255 ratios t/256: the first eight bisection steps of Algorithm 1 can only ask for
  *   those, so the search serves them from that table (same lengths, same p, same iteration count as
  *   walking the cumulative sums) and reads the sums only from the ninth step on. */

@@ -104,7 +104,7 @@ int prefixkv_select(int B, int L, int N, const float* importance, const pkv_sele
         return PKV_ERR_NULL;
     if (B < 1 || L < 1 || L > kMaxL || N < 1 || N > kMaxN) return PKV_ERR_DIM;
     if (params->budget_tokens < 1 || params->tol_tokens < 0 || params->max_iters < 1) return PKV_ERR_BUDGET;
-    if (!ws || ws_bytes < select_ws_bytes(B, L, N)) return PKV_ERR_WORKSPACE;
+    if (!ws || ws_bytes < select_ws_bytes(B, L, N) || !aligned16(ws)) return PKV_ERR_WORKSPACE;
     const hipError_t e = launch_select(B, L, N, importance, *params, order, cum, prefix, lengths, p_out,
                                        iters, raw_total, status, ws, true, (hipStream_t)stream);
     return e == hipSuccess ? PKV_OK : PKV_ERR_HIP;

@@ -96,6 +96,7 @@ def test_select_argument_errors():
     assert call(iters=0) == 6
     assert call(ws=None) == 5
     assert call(wsb=3) == 5
+    assert call(ws=C.c_void_p(0x1004)) == 5       # the table of tabulated lengths is read 16 bytes at a time
 
 
 def test_select_static_argument_errors():
