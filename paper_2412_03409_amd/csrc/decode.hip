@@ -430,10 +430,33 @@ __device__ __forceinline__ int last_piece_class(int len, int S) {
     return kPlanClasses - 1 - c;
 }
 
+// sum over the workgroup and exclusive prefix of v (blockDim.x a multiple of 64, at most 1024): wavefront
+// shuffles and one pass over the wavefront totals
+__device__ __forceinline__ int plan_scan(int v, int* s_wave, int& total) {
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave, nw = blockDim.x / kWave;
+    int incl = v;
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int up = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += up;
+    }
+    __syncthreads();                         // s_wave may still be read from the previous call
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+    for (int w = 0; w < nw; ++w) {
+        const int t = s_wave[w];
+        if (w < wv) base += t;
+        tot += t;
+    }
+    total = tot;
+    return base + incl - v;
+}
+
 template <bool EV>
 __global__ void __launch_bounds__(kPlanThreads)
 decode_plan_kernel(DecodeParams p) {
-    __shared__ int s_red[kPlanThreads];
+    __shared__ int s_wave[kPlanThreads / kWave];
+    __shared__ int s_cls[kPlanClasses];
     const int tid = threadIdx.x, n = p.n_seg;
     const int nt = blockDim.x;               // a power of two, 64 .. kPlanThreads: no more wavefronts than the segments need
     const int per = (n + nt - 1) / nt;
@@ -441,49 +464,32 @@ decode_plan_kernel(DecodeParams p) {
     int* hdr = p.plan;
     int* arrive = p.plan + kPlanHdr;
     int* records = p.plan + p.record_word;
+    auto seg_of = [&](int i) { return (i / p.nl) * p.L + p.l0 + i % p.nl; };
+    // Up to kPlanThreads segments (the usual case) are one per thread: its state is read once and kept.
+    const bool single = per == 1;
+    SegState mine_ss;
+    if (single && lo < hi) mine_ss = seg_state<EV>(p, seg_of(lo));
+    auto state = [&](int i) { return single ? mine_ss : seg_state<EV>(p, seg_of(i)); };
+    if (tid < kPlanClasses) s_cls[tid] = 0;
     // Items are claimed from a counter in list order, so the list holds the full pieces first and the last
     // (shorter) piece of every segment at the end: the tail of the launch is made of small items.
-    int S = p.S0, total_full = 0, mine = 0;
+    int S = p.S0, total_full = 0, mine = 0, at = 0;
     for (;;) {
         mine = 0;
         for (int i = lo; i < hi; ++i) {
-            const int sl = (i / p.nl) * p.L + p.l0 + i % p.nl;
-            const int len = seg_state<EV>(p, sl).len;
+            const int len = state(i).len;
             const int np = (len + S - 1) / S;
             mine += np < 1 ? 0 : np - 1;      // full pieces; every segment has exactly one last piece
         }
-        s_red[tid] = mine;
-        __syncthreads();
-        for (int st = nt / 2; st > 0; st >>= 1) {
-            if (tid < st) s_red[tid] += s_red[tid + st];
-            __syncthreads();
-        }
-        total_full = s_red[0];
-        __syncthreads();
+        at = plan_scan(mine, s_wave, total_full);
         if (total_full + n <= p.pieces_cap || S >= (1 << 24)) break;
         S *= 2;
     }
-    // exclusive scan of the per-thread counts
-    s_red[tid] = mine;
-    __syncthreads();
-    for (int st = 1; st < nt; st <<= 1) {
-        const int v = tid >= st ? s_red[tid - st] : 0;
-        __syncthreads();
-        s_red[tid] += v;
-        __syncthreads();
-    }
-    int at = s_red[tid] - mine;
     const int total = total_full + n;
     const bool ok = total <= p.pieces_cap;   // cannot fail for pieces_cap >= n_seg
     // the last pieces go into the list by size class, largest first (the order inside a class is arbitrary;
-    // results do not depend on the order of the list)
-    __shared__ int s_cls[kPlanClasses];
-    if (tid < kPlanClasses) s_cls[tid] = 0;
-    __syncthreads();
-    for (int i = lo; i < hi; ++i) {
-        const int sl = (i / p.nl) * p.L + p.l0 + i % p.nl;
-        atomicAdd(&s_cls[last_piece_class(seg_state<EV>(p, sl).len, S)], 1);
-    }
+    // results do not depend on the order of the list); s_cls was cleared before the barriers of the scan
+    for (int i = lo; i < hi; ++i) atomicAdd(&s_cls[last_piece_class(state(i).len, S)], 1);
     __syncthreads();
     if (tid == 0) {
         int run = 0;
@@ -492,8 +498,8 @@ decode_plan_kernel(DecodeParams p) {
     __syncthreads();
     if (ok) {
         for (int i = lo; i < hi; ++i) {
-            const int sl = (i / p.nl) * p.L + p.l0 + i % p.nl;
-            const SegState ss = seg_state<EV>(p, sl);
+            const int sl = seg_of(i);
+            const SegState ss = state(i);
             int np = (ss.len + S - 1) / S;
             np = np < 1 ? 1 : np;
             const int last = total_full + atomicAdd(&s_cls[last_piece_class(ss.len, S)], 1);
