@@ -80,7 +80,8 @@ size_t prefixkv_workspace_bytes(int op, const pkv_shape *shape, int has_lse);
  *   q [dev] [B,L,H,N,D] with strides qs;  k [dev] [B,L,Hkv,N,D] with strides ks  (shape->dtype)
  *   scale [dev] fp32 [L]
  *   lse [dev] fp32 [B,L,H,N] = log sum_{j<=m} exp(scale*q_m.k_j) of every causal row if the caller
- *       already has it from its prefill attention, or NULL: it is then computed here (second pass).
+ *       already has it from its prefill attention, or NULL: it is then computed here (a first sweep over
+ *       the keys inside the same kernel).
  *   importance [dev] fp32 [B,L,N], out (dense).
  * bf16 inputs use bf16 MFMA with fp32 accumulation; exp and all sums are fp32. */
 int prefixkv_importance(const pkv_shape *shape, const void *q, pkv_strides qs, const void *k,
@@ -89,7 +90,7 @@ int prefixkv_importance(const pkv_shape *shape, const void *q, pkv_strides qs, c
 
 /* ---- The step before the path: causal prefill attention that hands its row log-sum-exp to stage 1
  * (Sec. 3.1: the prefill phase attends over the whole prompt; Sec. 3.2 defines the importance on the
- * same score matrix, so a prefill kernel that keeps lse saves stage 1 one of its two passes).
+ * same score matrix, so a prefill kernel that keeps lse saves stage 1 one of its two sweeps over the keys).
  *   out[b,l,h,m,:] = sum_{n<=m} softmax_{j<=m}(scale[l] * q_m.k_j)[n] * v[b,l,g(h),n,:]
  *   lse[b,l,h,m]   = log sum_{j<=m} exp(scale[l] * q_m.k_j)         (natural log, fp32)
  * bf16 storage only (PKV_ERR_UNSUPPORTED otherwise); both products on bf16 MFMA with fp32 accumulation,
