@@ -139,10 +139,47 @@ struct FusedParams {
     float* partial;            // [B*L*H][G][N]: workgroup g's column sums of keys [0, min(N, 32*(T-4g)))
 };
 
+// barrier that orders LDS traffic only: loads from global memory that are still in flight stay in flight
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+// one wavefront copies a whole stage (rolled loop: a few address registers)
+template <int D>
+__device__ __forceinline__ void copy_stage(const bf16_t* base, int64_t ld, int row0, int N, unsigned char* lds, int lane) {
+    using S1 = Stage<D, 1>;
+#pragma unroll 2
+    for (int inst = 0; inst < S1::PIECES; ++inst) {
+        const int L = inst * 64 + lane;
+        const int row = L / S1::CPR, pos = L % S1::CPR;
+        const int c = pos ^ ((row / S1::RPB) & (S1::CPR - 1));
+        int grow = row0 + row;
+        grow = grow < N ? grow : N - 1;
+        const bf16_t* g = base + ((uint32_t)grow * (uint32_t)ld + (uint32_t)(c * 8));
+        __builtin_amdgcn_global_load_lds((glb_void_t*)g, (lds_void_t*)(lds + inst * 1024), 16, 0, 0);
+    }
+}
+template <int D>
+__device__ __forceinline__ void load_stationary_one(bf16x8 (&f)[D / 16], const bf16_t* base, int64_t ld, int row0,
+                                                    int N, int lane, bool flip) {
+    const uint32_t sgn = flip ? 0x80008000u : 0u;
+    int row = row0 + (lane & 31);
+    row = row < N ? row : N - 1;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+        uint4 v = *(const uint4*)(base + (int64_t)row * ld + 16 * kk + 8 * (lane >> 5));
+        v.x ^= sgn; v.y ^= sgn; v.z ^= sgn; v.w ^= sgn;
+        f[kk] = as_bf16x8(v);
+    }
+}
+
 // WV wavefronts per workgroup; OCC wavefronts per SIMD the register allocation must allow.
-template <int D, bool HAS_LSE, int WV, int OCC>
+// SPREAD (short prompts without a given lse, last wavefront without tiles): see the start of the kernel.
+template <int D, bool HAS_LSE, int WV, int OCC, bool SPREAD>
 __global__ void __launch_bounds__(WV * kWave, OCC)
 importance_fused_kernel(FusedParams p) {
+    static_assert(!(SPREAD && HAS_LSE), "the spread start belongs to the first sweep");
     constexpr int KS = D / 16;
     constexpr int NSUB = kStage / 32;
     using St = Stage<D, WV>;
@@ -178,9 +215,25 @@ importance_fused_kernel(FusedParams p) {
     // s_tile{(t - t0) & 1}; the stage of step t+1 is copied into the other buffer meanwhile.
     const int t0 = HAS_LSE ? S : 0;
 
-    St::issue(kb, p.ks.n, 0, p.N, s_tile0, wv, lane);
+    // SPREAD: the first sweep walks the key stages downwards: the late tiles are needed first (the last stage by
+    // the two latest tiles only), the early tiles not before the low stages, so the queries are requested late
+    // tile first and arrive while the first stages are worked on, instead of all before the first product.
+    // For that the key copies are issued by the last wavefront alone -- the launcher picks this form only when
+    // that wavefront has no tiles (fewer pairs than wavefronts) -- and the barriers order LDS traffic only: a
+    // wavefront's query loads then stay in flight across barriers.  (Measured: -2..3 % at 680 positions; with
+    // every wavefront busy and several workgroups per head it loses, 80 against 73 ms at 8192 positions.)
+    const bool copier = wv == WV - 1;
     bf16x8 bq[2][KS];
-    load_stationary<D>(bq, qb, p.qs.n, tE < 0 ? 0 : qlo0, tL < 0 ? 0 : qlo1, p.N, lane, flip);
+    if constexpr (SPREAD) {
+        if (copier) copy_stage<D>(kb, p.ks.n, (S - 1) * kStage, p.N, s_tile0, lane);
+        else {
+            if (tL >= 0) load_stationary_one<D>(bq[1], qb, p.qs.n, qlo1, p.N, lane, flip);
+            if (tE >= 0) load_stationary_one<D>(bq[0], qb, p.qs.n, qlo0, p.N, lane, flip);
+        }
+    } else {
+        St::issue(kb, p.ks.n, 0, p.N, s_tile0, wv, lane);
+        load_stationary<D>(bq, qb, p.qs.n, tE < 0 ? 0 : qlo0, tL < 0 ? 0 : qlo1, p.N, lane, flip);
+    }
     float mrun[2] = {-INFINITY, -INFINITY}, srun[2] = {0.f, 0.f};
     if (HAS_LSE) {
         const float* lse = p.lse_in + (size_t)head * p.N;
@@ -193,8 +246,13 @@ importance_fused_kernel(FusedParams p) {
             }
         }
     }
-    wait_async_copies();
-    __syncthreads();
+    if constexpr (SPREAD) {
+        if (copier) wait_async_copies();
+        lds_barrier();
+    } else {
+        wait_async_copies();
+        __syncthreads();
+    }
     int par = 0;
 
     // sweep 1, one key stage: S^T = K.Q^T, a lane holds one query and 16 keys
@@ -326,9 +384,47 @@ importance_fused_kernel(FusedParams p) {
             par ^= 1;
         }
     };
-    for (int t = t0; t < 2 * S; t += 2) {
-        step(s_tile0, s_tile1, t);
-        if (t + 1 < 2 * S) step(s_tile1, s_tile0, t + 1);
+    if constexpr (!SPREAD) {
+        for (int t = t0; t < 2 * S; t += 2) {
+            step(s_tile0, s_tile1, t);
+            if (t + 1 < 2 * S) step(s_tile1, s_tile0, t + 1);
+        }
+    } else {
+        // step u of sweep 1 works on stage S-1-u, step u of sweep 2 on stage u; buffers alternate throughout
+        auto flush = [&](int s) {
+            if (threadIdx.x < kStage) {
+                const int sub = threadIdx.x >> 5, c32 = threadIdx.x & 31;
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < WV; ++w) sum += s_red[par][w][sub][c32];
+                const int n = s * kStage + threadIdx.x;
+                if (n < klim) part[n] = sum;
+            }
+            par ^= 1;
+        };
+        auto step1 = [&](const unsigned char* cur, unsigned char* nxt, int u) {
+            if (copier) copy_stage<D>(kb, p.ks.n, (u + 1 < S ? S - 2 - u : 0) * kStage, p.N, nxt, lane);
+            stage1(cur, S - 1 - u);
+            if (u == S - 1) finish_lse();
+            if (copier) wait_async_copies();
+            lds_barrier();
+        };
+        auto step2 = [&](const unsigned char* cur, unsigned char* nxt, int u) {
+            if (copier && u + 1 < S) copy_stage<D>(kb, p.ks.n, (u + 1) * kStage, p.N, nxt, lane);
+            stage2(cur, u);
+            if (copier) wait_async_copies();
+            lds_barrier();
+            flush(u);
+        };
+        int sel = 0;
+        for (int u = 0; u < S; ++u, sel ^= 1) {
+            if (sel == 0) step1(s_tile0, s_tile1, u); else step1(s_tile1, s_tile0, u);
+        }
+        // every query load has been consumed by now; saying so keeps the second sweep free of waits for them
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        for (int u = 0; u < S; ++u, sel ^= 1) {
+            if (sel == 0) step2(s_tile0, s_tile1, u); else step2(s_tile1, s_tile0, u);
+        }
     }
 }
 
@@ -517,12 +613,16 @@ hipError_t launch_importance(const pkv_shape& s, const void* q, Strides qs, cons
     const long long nblk = p.chunk * kXcds;
     if (nblk > 0x7fffffffll) return hipErrorInvalidValue;
     const dim3 grid((unsigned)nblk), block(kFusedWaves * kWave);
+    const bool spread = !lse && p.G == 1 && p.npairs < kFusedWaves;   // the last wavefront only copies
     if (lse) {
-        if (s.D == 128) hipLaunchKernelGGL((importance_fused_kernel<128, true, kFusedWaves, kFusedOcc>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((importance_fused_kernel<64, true, kFusedWaves, kFusedOcc>), grid, block, 0, st, p);
+        if (s.D == 128) hipLaunchKernelGGL((importance_fused_kernel<128, true, kFusedWaves, kFusedOcc, false>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((importance_fused_kernel<64, true, kFusedWaves, kFusedOcc, false>), grid, block, 0, st, p);
+    } else if (spread) {
+        if (s.D == 128) hipLaunchKernelGGL((importance_fused_kernel<128, false, kFusedWaves, kFusedOcc, true>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((importance_fused_kernel<64, false, kFusedWaves, kFusedOcc, true>), grid, block, 0, st, p);
     } else {
-        if (s.D == 128) hipLaunchKernelGGL((importance_fused_kernel<128, false, kFusedWaves, kFusedOcc>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((importance_fused_kernel<64, false, kFusedWaves, kFusedOcc>), grid, block, 0, st, p);
+        if (s.D == 128) hipLaunchKernelGGL((importance_fused_kernel<128, false, kFusedWaves, kFusedOcc, false>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((importance_fused_kernel<64, false, kFusedWaves, kFusedOcc, false>), grid, block, 0, st, p);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(head_mean_fused_kernel, dim3((unsigned)((total + kMeanKeys - 1) / kMeanKeys)),

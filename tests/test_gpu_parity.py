@@ -49,6 +49,10 @@ def check_importance(got, want):
     (1, 1, 2, 2, 1, 128, torch.bfloat16),      # a single position
     (1, 2, 2, 1, 31, 128, torch.bfloat16),     # less than one MFMA tile
     (1, 1, 3, 3, 680, 128, torch.bfloat16),    # the LLaVA prompt length
+    (1, 1, 2, 2, 704, 128, torch.bfloat16),    # 11 tile pairs: the last wavefront only copies (spread start)
+    (1, 2, 2, 1, 736, 64, torch.bfloat16),     # 12 pairs: every wavefront of the one workgroup has tiles
+    (1, 1, 2, 2, 768, 128, torch.bfloat16),    # 24 tiles, still one workgroup per head
+    (1, 1, 2, 2, 770, 128, torch.bfloat16),    # 25 tiles: two workgroups per head
     (1, 1, 2, 2, 1100, 128, torch.bfloat16),   # beyond 1024
     (1, 1, 2, 1, 2300, 128, torch.bfloat16),   # long prompt: the software-pipelined stages below the diagonal
     (1, 1, 1, 1, 2100, 64, torch.bfloat16),    # ... with D = 64
