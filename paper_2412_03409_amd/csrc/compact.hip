@@ -1,113 +1,133 @@
 // Stage 4a: gather the kept K/V rows of every layer into the ragged per-layer cache (Sec. 3.2: the
 // top R_l proportion is retained in each head of layer l; all heads of a layer share one index set).
 //
-//  compact_plan_kernel   one workgroup per (sequence, layer): segment offset (sum of the capacities of
-//                        the segments before it), capacity, and the kept positions in ascending order
-//                        (flag array in LDS -> exclusive scan -> scatter).
-//  compact_gather_kernel streams whole rows (16 B per lane) from K/V into the segment.  Pure HBM traffic.
+//  compact_fused_kernel   one launch: every workgroup of a (sequence, layer, kv head, 64-row chunk) derives the
+//                         segment's offset and its kept positions in ascending order (flag array in LDS ->
+//                         exclusive scan -> scatter) and streams its whole rows (16 B per lane) from K/V into
+//                         the segment.  Pure HBM traffic.
+//  merge_position_kernel  the positional-distance merge of Sec. 4.3 on top of a compacted cache.
 #include "pkv_common.hpp"
 
 namespace pkv {
 
-__device__ __forceinline__ int block_excl_scan_i32(int v, int* s_wave, int& total) {
-    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave, nw = blockDim.x / kWave;
-    int incl = v;
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int up = __shfl_up(incl, d, kWave);
-        if (lane >= d) incl += up;
+// Source rows are read once.  Loads that bypass the caches (nontemporal) pay when K and V together are far
+// larger than the 256 MB last-level cache (from 2 GiB on, inside the whole pipeline: -5 % ... -7 %; below that
+// they cost up to 20 %), so the launcher chooses.  Nontemporal stores of the cache rows were 2-5 % slower inside
+// the pipeline at every size (and faster only when the same call is repeated back to back), so stores are plain.
+typedef __attribute__((ext_vector_type(4))) unsigned int cu32x4_t;
+template <bool NT>
+__device__ __forceinline__ uint4 ld_row16(const unsigned char* p) {
+    if constexpr (NT) {
+        const cu32x4_t t = __builtin_nontemporal_load((const cu32x4_t*)p);
+        return make_uint4(t.x, t.y, t.z, t.w);
+    } else {
+        return *(const uint4*)p;
     }
-    __syncthreads();  // s_wave may still be in use by a previous call
-    if (lane == kWave - 1) s_wave[wv] = incl;
-    __syncthreads();
-    int base = 0, tot = 0;
-    for (int w = 0; w < nw; ++w) {
-        const int t = s_wave[w];
-        if (w < wv) base += t;
-        tot += t;
-    }
-    total = tot;
-    return base + incl - v;
 }
 
-__global__ void compact_plan_kernel(int N, int nseg, const int32_t* __restrict__ order,
-                                    const int32_t* __restrict__ lengths, int decode_capacity,
-                                    int64_t* __restrict__ seg_off, int32_t* __restrict__ caps,
-                                    int32_t* __restrict__ kept_pos, int32_t* __restrict__ lens) {
-    extern __shared__ unsigned char s_flag[];  // N flags
-    __shared__ int s_wave[16];
-    __shared__ long long s_off[16];
-    const int tid = threadIdx.x, nt = blockDim.x, seg = blockIdx.x;
-    const int lane = tid & (kWave - 1), wv = tid / kWave, nw = nt / kWave;
+// One launch.  Every workgroup of a (segment, kv head, chunk) builds the segment's list of kept positions
+// itself in LDS (flag per position -> counts -> exclusive scan -> scatter: ascending positions) and then copies
+// its chunks of 64 rows, K and V, 16 bytes per lane (LPR lanes cover a row, so the workgroup moves 256/LPR
+// whole rows per instruction); the workgroup of kv head 0, chunk 0 also writes the segment's offset (sum of the
+// lengths and capacities of the segments before it), capacity, length and positions for the later stages.
+// The redundant plans read `order` (4 bytes per kept row) from the L2 and cost less than the separate planning
+// launch they replace (7B shape, batch 1: 35 -> 31 us; N = 8192: 171 -> 163 us).  Workgroups whose chunk lies
+// beyond the segment's length leave at once; beyond 16 chunks a workgroup walks further chunks.
+template <int LPR, bool NTL>
+__global__ void __launch_bounds__(256)
+compact_fused_kernel(int N, int nchunk, int Hkv, int L, int row_bytes, const unsigned char* __restrict__ k, Strides ks,
+                     const unsigned char* __restrict__ v, Strides vs, int esize, const int32_t* __restrict__ order,
+                     const int32_t* __restrict__ lengths, int decode_capacity, int64_t* __restrict__ seg_off,
+                     int32_t* __restrict__ caps, int32_t* __restrict__ lens, int32_t* __restrict__ kept_pos,
+                     unsigned char* __restrict__ kc, unsigned char* __restrict__ vc) {
+    constexpr int kRows = 64;
+    constexpr int RPI = 256 / LPR;
+    extern __shared__ int s_dyn[];                  // kept positions (N ints), then the flags (N rounded up to 4 bytes)
+    __shared__ int s_wave[4];
+    __shared__ long long s_off[4];
+    int* s_kept = s_dyn;
+    uint32_t* s_flag = (uint32_t*)(s_dyn + N);
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    // chunk index fastest: neighbouring workgroups read neighbouring source rows and write adjacent slots.
+    // `nchunk` is odd (see the launcher), so the chunks of successive (segment, head) pairs rotate over the XCDs.
+    const int chunk = blockIdx.x % nchunk, h = (blockIdx.x / nchunk) % Hkv, seg = blockIdx.x / (nchunk * Hkv);
+    int klen = lengths[seg];
+    klen = klen < 0 ? 0 : (klen > N ? N : klen);
+    const bool scribe = h == 0 && chunk == 0;
+    if (chunk * kRows >= klen && !scribe) return;
 
-    // token offset of this segment = sum of (length + capacity) of all segments before it
+    // token offset of the segment = sum of (length + capacity) of all segments before it
     long long acc = 0;
-    for (int i = tid; i < seg; i += nt) acc += (long long)lengths[i] + decode_capacity;
+    for (int i = tid; i < seg; i += 256) acc += (long long)lengths[i] + decode_capacity;
+    const int32_t* ord = order + (size_t)seg * N;
+    int pos_mine[4];                                 // the first 1024 entries of the list are requested at once
+#pragma unroll
+    for (int u = 0; u < 4; ++u) pos_mine[u] = tid + 256 * u < klen ? ord[tid + 256 * u] : -1;
+    const int nword = (N + 3) / 4;
+    for (int i = tid; i < nword; i += 256) s_flag[i] = 0;
     for (int d = 32; d > 0; d >>= 1) {
         const uint32_t lo = __shfl_xor((uint32_t)acc, d, kWave);
         const uint32_t hi = __shfl_xor((uint32_t)((unsigned long long)acc >> 32), d, kWave);
         acc += (long long)(((unsigned long long)hi << 32) | lo);
     }
     if (lane == 0) s_off[wv] = acc;
-    for (int i = tid; i < N; i += nt) s_flag[i] = 0;
     __syncthreads();
-    long long off = 0;
-    for (int w = 0; w < nw; ++w) off += s_off[w];
-
-    int klen = lengths[seg];
-    klen = klen < 0 ? 0 : (klen > N ? N : klen);
-    const int32_t* ord = order + (size_t)seg * N;
-    for (int j = tid; j < klen; j += nt) {
+    const long long off = s_off[0] + s_off[1] + s_off[2] + s_off[3];
+    unsigned char* fb = (unsigned char*)s_flag;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (pos_mine[u] >= 0 && pos_mine[u] < N) fb[pos_mine[u]] = 1;
+    for (int j = tid + 1024; j < klen; j += 256) {
         const int pos = ord[j];
-        if (pos >= 0 && pos < N) s_flag[pos] = 1;
+        if (pos >= 0 && pos < N) fb[pos] = 1;
     }
     __syncthreads();
-    const int E = (N + nt - 1) / nt;
-    const int lo = tid * E, hi = min(lo + E, N);
+    // a thread owns E consecutive flag words
+    const int E = (nword + 255) / 256;
+    const int w_lo = tid * E, w_hi = min(w_lo + E, nword);
     int cnt = 0;
-    for (int i = lo; i < hi; ++i) cnt += s_flag[i];
-    int total;
-    int at = block_excl_scan_i32(cnt, s_wave, total);
-    for (int i = lo; i < hi; ++i)
-        if (s_flag[i]) kept_pos[off + at++] = i;
-    if (tid == 0) {
-        seg_off[seg] = off;
-        caps[seg] = klen + decode_capacity;
-        lens[seg] = klen;
+    for (int w = w_lo; w < w_hi; ++w) cnt += (int)((s_flag[w] * 0x01010101u) >> 24);
+    int incl = cnt;
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int up = __shfl_up(incl, d, kWave);
+        if (lane >= d) incl += up;
     }
-}
-
-// A workgroup copies kRows kept rows of one (segment, kv head) at a time, K and V; `nchunk` workgroups share
-// a (segment, kv head) and stride over its chunks, so no workgroup is launched for rows that were not kept.
-// LPR lanes cover a row with one 16-byte load each, so a wavefront moves 64/LPR whole rows per instruction.
-template <int LPR>
-__global__ void __launch_bounds__(256)
-compact_gather_kernel(int nchunk, int Hkv, int L, int row_bytes, const unsigned char* __restrict__ k, Strides ks,
-                      const unsigned char* __restrict__ v, Strides vs, int esize,
-                      const int64_t* __restrict__ seg_off, const int32_t* __restrict__ caps,
-                      const int32_t* __restrict__ lens, const int32_t* __restrict__ kept_pos,
-                      unsigned char* __restrict__ kc, unsigned char* __restrict__ vc) {
-    constexpr int kRows = 64;
-    constexpr int RPI = 256 / LPR;  // rows per workgroup-wide instruction
-    const int h = (blockIdx.x / nchunk) % Hkv, seg = blockIdx.x / (nchunk * Hkv);
-    const int len = lens[seg];
-    if ((int)(blockIdx.x % nchunk) * kRows >= len) return;
+    if (lane == kWave - 1) s_wave[wv] = incl;
+    __syncthreads();
+    int at = incl - cnt;
+    for (int w = 0; w < wv; ++w) at += s_wave[w];
+    const int len = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];   // = klen when `order` is a permutation
+    for (int w = w_lo; w < w_hi; ++w) {
+        const uint32_t f = s_flag[w];
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+            if ((f >> (8 * x)) & 1) s_kept[at++] = 4 * w + x;
+    }
+    __syncthreads();
+    if (scribe) {
+        for (int j = tid; j < len; j += 256) kept_pos[off + j] = s_kept[j];
+        if (tid == 0) {
+            seg_off[seg] = off;
+            caps[seg] = klen + decode_capacity;
+            lens[seg] = klen;
+        }
+    }
     const int b = seg / L, l = seg % L;
-    const int64_t off = seg_off[seg];
-    const int cap = caps[seg];
-    const int sub = threadIdx.x % LPR, rsel = threadIdx.x / LPR;
+    const int cap = klen + decode_capacity;
+    const int sub = tid % LPR, rsel = tid / LPR;
     const unsigned char* kb = k + (ks.b * b + ks.l * l + ks.h * h) * (int64_t)esize;
     const unsigned char* vb = v + (vs.b * b + vs.l * l + vs.h * h) * (int64_t)esize;
-    const int64_t dst0 = (off * Hkv + (int64_t)h * cap) * row_bytes;
-    for (int r0 = (int)(blockIdx.x % nchunk) * kRows; r0 < len; r0 += nchunk * kRows) {
+    const int64_t dst0 = ((int64_t)off * Hkv + (int64_t)h * cap) * row_bytes;
+    for (int r0 = chunk * kRows; r0 < len; r0 += nchunk * kRows) {
         uint4 kr[kRows / RPI], vr[kRows / RPI];
 #pragma unroll
         for (int i = 0; i < kRows / RPI; ++i) {
             const int r = r0 + i * RPI + rsel;
-            kr[i] = vr[i] = make_uint4(0, 0, 0, 0);   // (defined on every path: the arrays stay in registers)
+            kr[i] = vr[i] = make_uint4(0, 0, 0, 0);
             if (r < len) {
-                const int pos = kept_pos[off + r];
-                kr[i] = *(const uint4*)(kb + ks.n * pos * (int64_t)esize + sub * 16);
-                vr[i] = *(const uint4*)(vb + vs.n * pos * (int64_t)esize + sub * 16);
+                const int pos = s_kept[r];
+                kr[i] = ld_row16<NTL>(kb + ks.n * pos * (int64_t)esize + sub * 16);
+                vr[i] = ld_row16<NTL>(vb + vs.n * pos * (int64_t)esize + sub * 16);
             }
         }
 #pragma unroll
@@ -267,34 +287,42 @@ hipError_t launch_merge_position(const pkv_shape& s, const void* k, Strides ks, 
     return hipGetLastError();
 }
 
+// Workgroups per (segment, kv head): one per 64-row chunk up to 16 chunks (1024 rows), made odd.  The hardware
+// deals consecutive workgroups out to the eight XCDs in turn; with an even count -- 16 above all -- chunk c of
+// every (segment, head) lands on the same XCD, and since most segments keep few rows the XCDs of the high
+// chunk indices see hardly any work (measured with 16: 2.3 instead of 4.3 TB/s from N = 1000 on).
+static int gather_chunks(int N) {
+    const int all_chunks = (N + 63) / 64;
+    const int nchunk = all_chunks < 16 ? all_chunks : 16;
+    return nchunk | 1;
+}
+
 hipError_t launch_compact(const pkv_shape& s, const void* k, Strides ks, const void* v, Strides vs,
                           const int32_t* order, const int32_t* lengths, int decode_capacity,
                           int64_t* seg_off, int32_t* caps, void* kc, void* vc, int32_t* kept_pos,
                           int32_t* lens, void*, hipStream_t st) {
     const int nseg = s.B * s.L;
-    const int nt = s.N > 2048 ? 1024 : 256;
-    hipLaunchKernelGGL(compact_plan_kernel, dim3(nseg), dim3(nt), (size_t)s.N, st, s.N, nseg, order,
-                       lengths, decode_capacity, seg_off, caps, kept_pos, lens);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
     const int esize = s.dtype == PKV_F32 ? 4 : 2;
     const int row_bytes = s.D * esize;
     const int lpr = row_bytes / 16;
-    // workgroups per (segment, kv head): one per chunk up to 16 (1024 rows); for longer prompts a workgroup
-    // walks further chunks -- most segments keep a small part of a long prompt, and workgroups that find
-    // nothing to do are not free (measured at N = 8192: 0.34 -> 0.27 ms; fewer than one workgroup per chunk
-    // at N = 680 is slower: the copies of a workgroup are one dependent chain)
-    const int all_chunks = (s.N + 63) / 64;
-    const int nchunk = all_chunks < 16 ? all_chunks : 16;
+    const int nchunk = gather_chunks(s.N);
     dim3 grid((uint32_t)((size_t)nchunk * s.Hkv * nseg));
-#define PKV_GATHER(LPR)                                                                                  \
-    hipLaunchKernelGGL(compact_gather_kernel<LPR>, grid, dim3(256), 0, st, nchunk, s.Hkv, s.L, row_bytes,       \
-                       (const unsigned char*)k, ks, (const unsigned char*)v, vs, esize, seg_off, caps,  \
-                       lens, kept_pos, (unsigned char*)kc, (unsigned char*)vc)
-    if (lpr == 8) PKV_GATHER(8);
-    else if (lpr == 16) PKV_GATHER(16);
-    else PKV_GATHER(32);
-#undef PKV_GATHER
+    const size_t lds = (size_t)s.N * 4 + (size_t)((s.N + 3) / 4) * 4;
+    const bool ntl = 2 * (size_t)nseg * s.Hkv * s.N * row_bytes >= ((size_t)1 << 31);   // K and V: 2 GiB or more
+#define PKV_FUSED(LPR, NTL)                                                                                        \
+    hipLaunchKernelGGL((compact_fused_kernel<LPR, NTL>), grid, dim3(256), lds, st, s.N, nchunk, s.Hkv, s.L, row_bytes, \
+                       (const unsigned char*)k, ks, (const unsigned char*)v, vs, esize, order, lengths,            \
+                       decode_capacity, seg_off, caps, lens, kept_pos, (unsigned char*)kc, (unsigned char*)vc)
+    if (ntl) {
+        if (lpr == 8) PKV_FUSED(8, true);
+        else if (lpr == 16) PKV_FUSED(16, true);
+        else PKV_FUSED(32, true);
+    } else {
+        if (lpr == 8) PKV_FUSED(8, false);
+        else if (lpr == 16) PKV_FUSED(16, false);
+        else PKV_FUSED(32, false);
+    }
+#undef PKV_FUSED
     return hipGetLastError();
 }
 

@@ -394,6 +394,8 @@ def test_merge_feature_matches_oracle(B, L, Hkv, N, D, frac):
     (2, 2, 2, 70, 64, torch.bfloat16, 0.33),
     (1, 2, 2, 100, 128, torch.float32, 1.0),
     (1, 3, 1, 8192, 128, torch.bfloat16, 0.1),
+    (1, 2, 2, 1500, 64, torch.bfloat16, 0.9),      # more kept rows than one round of 17 chunks: workgroups walk on
+    (2, 1, 3, 1024, 128, torch.float32, 1.0),      # a whole copy of a power-of-two prompt
 ])
 def test_compact_bit_exact(B, L, Hkv, N, D, dtype, frac):
     g = torch.Generator().manual_seed(N + D)
