@@ -307,6 +307,7 @@ hipError_t launch_compact(const pkv_shape& s, const void* k, Strides ks, const v
     const int lpr = row_bytes / 16;
     const int nchunk = gather_chunks(s.N);
     dim3 grid((uint32_t)((size_t)nchunk * s.Hkv * nseg));
+    static_assert((size_t)kMaxN * 5 + 256 <= 64 * 1024, "the position list and the flags of the longest prompt fit the default LDS limit");
     const size_t lds = (size_t)s.N * 4 + (size_t)((s.N + 3) / 4) * 4;
     const bool ntl = 2 * (size_t)nseg * s.Hkv * s.N * row_bytes >= ((size_t)1 << 31);   // K and V: 2 GiB or more
 #define PKV_FUSED(LPR, NTL)                                                                                        \
