@@ -78,8 +78,14 @@ prefill_attn_kernel(PrefillParams p) {
 
     const int heads = p.B * p.L * p.H;
     const int nqb = (p.N + kPfQueries - 1) / kPfQueries;
-    const int qb = nqb - 1 - (int)(blockIdx.x / heads);    // the long (late) query blocks start first
-    const int hh = blockIdx.x % heads;
+    // The query blocks of one head run next to each other on one XCD (the hardware deals consecutive workgroups
+    // out to the eight XCDs in turn) and share the head's K and V through that XCD's L2, as do the query heads
+    // of one KV head; within a head the long (late) query blocks start first.
+    const int per_xcd = (int)(gridDim.x / kXcds);         // a whole number of heads
+    const int j = (int)(blockIdx.x % kXcds) * per_xcd + (int)(blockIdx.x / kXcds);
+    const int qb = nqb - 1 - j % nqb;
+    const int hh = j / nqb;
+    if (hh >= heads) return;
     const int h = hh % p.H, l = (hh / p.H) % p.L, b = hh / (p.H * p.L);
     const int kvh = h / (p.H / p.Hkv);
     const bf16_t* qbase = p.q + p.qs.b * b + p.qs.l * l + p.qs.h * h;
@@ -258,7 +264,9 @@ hipError_t launch_prefill_attn(const pkv_shape& s, const void* q, Strides qs, co
     p.scale = scale; p.out = (bf16_t*)out; p.lse = lse;
     const long long heads = (long long)s.B * s.L * s.H;
     const long long nqb = (s.N + kPfQueries - 1) / kPfQueries;
-    const dim3 grid((unsigned)(heads * nqb));
+    const long long nblk = (heads + kXcds - 1) / kXcds * nqb * kXcds;   // whole heads per XCD
+    if (nblk > 0x7fffffffll) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)nblk);
     if (s.D == 128) hipLaunchKernelGGL(prefill_attn_kernel<128>, grid, dim3(256), 0, st, p);
     else hipLaunchKernelGGL(prefill_attn_kernel<64>, grid, dim3(256), 0, st, p);
     return hipGetLastError();
